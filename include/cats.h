@@ -1,0 +1,163 @@
+/*
+ * cats.h - C ABI of the MI355X (gfx950) draft-tree verification library.
+ *
+ * The library runs the target verification pass of cascaded tree speculation
+ * (paper Sec. 3.2 "Cascaded verification design", paragraph "Target
+ * verification pass"; Algorithm 1, Stage 3 and the walk / bonus / commit steps
+ * after it; tree mask of Fig. 4, right): all T nodes of a draft tree go through
+ * a range of decoder layers in one batched pass, every layer's weights being
+ * read from HBM once; each node attends to the committed context and to its own
+ * ancestors; the longest root-descending chain whose tokens match the target's
+ * greedy choices is accepted, one bonus token is produced, and the KV cache is
+ * rolled back to the accepted path.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its comment says HOST.
+ *  - bf16 = the upper 16 bits of an IEEE float32.  Matrices are row-major
+ *    [out][in] (y = x W^T).  The layer is pre-norm RMSNorm + multi-head
+ *    attention with rotary embedding (half-split pairing, dimension j pairs with
+ *    j + head_dim/2) + SwiGLU feed-forward, no biases.
+ *  - The caller owns all weights, caches, inputs and outputs; the library only
+ *    borrows them until the enqueued work has run.  A cats_ctx owns scratch
+ *    memory sized at creation; no call allocates after cats_create.
+ *  - Work is enqueued on the given HIP stream (a hipStream_t passed as void*,
+ *    NULL = default stream) and the call returns without waiting, except where
+ *    a HOST output pointer is given (then the call synchronises the stream).
+ *  - Every function returns CATS_OK (0) or a negative cats_status.  Arguments are
+ *    validated on the host before anything is enqueued; a call that fails has
+ *    enqueued nothing.
+ *  - Calls that use one cats_ctx must not overlap in time (they share scratch).
+ */
+#ifndef CATS_H
+#define CATS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CATS_MAX_TREE 128  /* largest tree (nodes incl. root)                  */
+#define CATS_MAX_DEPTH 16  /* deepest node; an accepted path has <= 17 entries */
+#define CATS_MAX_LAYERS 128
+
+typedef enum {
+    CATS_OK = 0,
+    CATS_EINVAL = -1,    /* null pointer, bad shape, malformed tree, token out of range */
+    CATS_ECAPACITY = -2, /* ctx_len + T exceeds max_ctx                                  */
+    CATS_ESTATE = -3,    /* no tree has been set                                         */
+    CATS_EHIP = -4       /* a HIP runtime call failed                                    */
+} cats_status;
+
+typedef struct cats_ctx cats_ctx;
+
+/* Model shape.  Requirements: hidden == n_heads*head_dim, head_dim == 64 or 128,
+ * hidden % 64 == 0, ffn % 16 == 0, max_ctx % 64 == 0, 1 <= max_tree <= CATS_MAX_TREE. */
+typedef struct {
+    int32_t n_layers, hidden, n_heads, head_dim, ffn, vocab;
+    int32_t max_ctx;  /* rows each KV cache holds                         */
+    int32_t max_tree; /* largest T this context will be asked to verify   */
+    float rms_eps, rope_base;
+} cats_model_desc;
+
+/* One decoder layer, bf16.  wq/wk/wv/wo: [hidden][hidden]; w_gate/w_up:
+ * [ffn][hidden]; w_down: [hidden][ffn]; g_attn/g_ffn: RMSNorm gains [hidden]. */
+typedef struct {
+    const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down, *g_attn, *g_ffn;
+} cats_layer_weights;
+
+/* One layer's KV cache, bf16.  k: [n_heads][max_ctx][head_dim], keys stored after
+ * rotation.  v: [n_heads][head_dim][max_ctx], i.e. values stored TRANSPOSED so
+ * that the row (context) index is the contiguous one.  Rows [0, ctx_len) are the
+ * committed context; a verify call writes rows ctx_len .. ctx_len+T-1. */
+typedef struct {
+    void *k, *v;
+} cats_kv_layer;
+
+/* A draft tree in topological order: HOST arrays of n entries, copied during
+ * cats_set_tree.  parent[0] = -1, 0 <= parent[i] < i, depth[0] = 0,
+ * depth[i] = depth[parent[i]] + 1 <= CATS_MAX_DEPTH, 0 <= token[i] < vocab.
+ * Node 0 is the last committed token (its K/V is not in the cache yet); every
+ * other node carries a candidate token judged by the target's prediction at
+ * its parent. */
+typedef struct {
+    const int32_t *token, *parent, *depth;
+    int32_t n;
+} cats_tree;
+
+/* Outcome of greedy acceptance (Algorithm 1: walk, bonus token, commit). */
+typedef struct {
+    int32_t n_accepted;                 /* accepted candidates = depth of the last accepted node */
+    int32_t path[CATS_MAX_DEPTH + 1];   /* node indices, root first; n_accepted+1 valid, rest -1  */
+    int32_t tokens[CATS_MAX_DEPTH + 1]; /* token ids of those nodes                               */
+    int32_t bonus_token;                /* target's argmax at the last accepted node              */
+    int32_t new_ctx_len;                /* ctx_len + n_accepted + 1                               */
+} cats_accept_result;
+
+/* Create / destroy a context (allocates all scratch for the given shape on the
+ * current device).  HOST pointers. */
+int cats_create(const cats_model_desc *desc, cats_ctx **out);
+int cats_destroy(cats_ctx *ctx);
+
+/* Validate a tree and upload it (tree ingest; the ancestor sets that form the
+ * tree attention mask of Fig. 4 are derived from parent[] on the device).
+ * Synchronous with respect to the host arrays: they may be freed on return. */
+int cats_set_tree(cats_ctx *ctx, const cats_tree *tree, void *stream);
+
+/* One decoder layer over all T tree nodes (Algorithm 1, Stage 3, one layer of
+ * M_{L_SV+1 : L_total}): hidden <- hidden + Attn(RMSNorm(hidden)) then
+ * hidden <- hidden + FFN(RMSNorm(hidden)).  hidden: float32 [T][hidden], in/out
+ * (the residual stream is kept in float32).  Node i is rotated at position
+ * ctx_len + depth[i]; its key/value go to cache row ctx_len + i. */
+int cats_verify_layer(cats_ctx *ctx, const cats_layer_weights *w, float *hidden,
+                      const cats_kv_layer *kv, int32_t ctx_len, void *stream);
+
+/* Tree-masked attention alone (Fig. 4 right-lower; "tree attention mask" of the
+ * target verification pass).  q: bf16 [T][hidden], already rotated; kv rows
+ * ctx_len .. ctx_len+T-1 must already hold the tree nodes' keys/values.
+ * out: bf16 [T][hidden].  Node i sees rows [0, ctx_len) and rows ctx_len + a
+ * for a in ancestors(i) + {i}. */
+int cats_tree_attention(cats_ctx *ctx, const void *q, const cats_kv_layer *kv, int32_t ctx_len,
+                        void *out, void *stream);
+
+/* Greedy acceptance and KV roll-back (Algorithm 1: "Walk the tree to find the
+ * longest accepted prefix", bonus token, "Roll back KV ... along the accepted
+ * path").  node_argmax: int32 [T], the target's greedy token at every node.
+ * kv: HOST array indexed by layer; layers [layer_begin, layer_end) are
+ * compacted: row ctx_len + path[k] moves to row ctx_len + k.  Rows from
+ * new_ctx_len on are left undefined.  out_dev: device result (required);
+ * out_host: optional HOST copy (the call then waits for the stream). */
+int cats_accept_and_compact(cats_ctx *ctx, const int32_t *node_argmax, const cats_kv_layer *kv,
+                            int32_t layer_begin, int32_t layer_end, int32_t ctx_len,
+                            cats_accept_result *out_dev, cats_accept_result *out_host,
+                            void *stream);
+
+/* A whole verify step: input rows (embedding lookup of the tree tokens when
+ * `embed` [vocab][hidden] bf16 is given, else `hidden_in` float32 [T][hidden],
+ * the stage-3 "T.hidden_states"), layers [layer_begin, layer_end) of `layers`
+ * (HOST array indexed by layer), final RMSNorm (g_final) + LM head (w_lm
+ * [vocab][hidden]) + per-node argmax, then acceptance and compaction as above.
+ * Optional device outputs: hidden_out float32 [T][hidden] (residual stream after
+ * the last layer), logits_out float32 [T][vocab], argmax_out int32 [T],
+ * margin_out float32 [T] (gap between the two largest logits of each node). */
+int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t layer_begin,
+                     int32_t layer_end, const void *embed, const float *hidden_in,
+                     const void *g_final, const void *w_lm, const cats_kv_layer *kv,
+                     int32_t ctx_len, float *hidden_out, float *logits_out, int32_t *argmax_out,
+                     float *margin_out, cats_accept_result *out_dev, cats_accept_result *out_host,
+                     void *stream);
+
+/* Final RMSNorm + LM head + argmax alone (Algorithm 1: p_tgt = softmax(H(H_tgt));
+ * greedy acceptance needs only the argmax).  hidden: float32 [T][hidden]. */
+int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, const void *g_final, const void *w_lm,
+                        float *logits_out, int32_t *argmax_out, float *margin_out, void *stream);
+
+/* Name of the dominant (weight-streaming) kernel as it appears in profiler
+ * output, and the text of a status code.  HOST strings, never freed. */
+const char *cats_gemm_kernel_name(void);
+const char *cats_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CATS_H */

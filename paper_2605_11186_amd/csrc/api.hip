@@ -1,0 +1,489 @@
+// Host side of the C ABI: argument validation, scratch ownership and the order
+// in which one verify step's kernels are enqueued (paper Algorithm 1, Stage 3
+// through the commit step).
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "common.hpp"
+
+struct cats_ctx {
+    cats_model_desc d;
+    int device;
+    // uploaded tree (device) and its host copy
+    int32_t *token, *parent, *depth;
+    int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
+    int T;  // 0 = no tree set
+    // scratch
+    float* x;        // [max_tree][H] residual stream
+    bf16_t* xn;      // [max_tree][H] normalised activations (GEMM input)
+    bf16_t* q;       // [max_tree][H]
+    bf16_t* attn;    // [max_tree][H]
+    bf16_t* hact;    // [max_tree][F]
+    float* part;     // split-K partial sums
+    size_t part_elems;
+    float2* rope_cs;  // [max_tree][d/2]
+    float* attn_po;
+    float* attn_pml;
+    int attn_max_chunks;
+    int32_t* amax;   // [max_tree]
+    char* flat;      // the single allocation behind all of the above
+};
+
+namespace {
+
+thread_local hipError_t g_last_hip = hipSuccess;
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip = e;
+    return CATS_EHIP;
+}
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return hip_fail(e_);     \
+    } while (0)
+
+inline size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+
+// split-K factor: enough workgroups to give every CU a few, slices a multiple of
+// the kernel's K chunk.  CATS_GEMM_WGS overrides the target workgroup count.
+int target_wgs() {
+    static int v = [] {
+        const char* e = std::getenv("CATS_GEMM_WGS");
+        const int n = e ? std::atoi(e) : 0;
+        return n > 0 ? n : 512;
+    }();
+    return v;
+}
+
+struct SplitPlan {
+    int splits, k_per_split;
+};
+SplitPlan plan_split(int N, int K) {
+    const int tiles = (N + GEMM_BN - 1) / GEMM_BN;
+    int want = std::max(1, std::min(16, target_wgs() / tiles));
+    const int chunks = (K + GEMM_KC - 1) / GEMM_KC;
+    want = std::min(want, chunks);
+    const int cps = (chunks + want - 1) / want;  // chunks per split
+    SplitPlan p;
+    p.k_per_split = cps * GEMM_KC;
+    p.splits = (chunks + cps - 1) / cps;
+    return p;
+}
+
+int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
+    const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
+    // aim at ~512 waves per launch: heads * chunks * query groups
+    const int tq = (c->T + 31) / 32;
+    int chunks = std::max(1, 512 / std::max(1, c->d.n_heads * tq));
+    chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
+    return (n_blocks + chunks - 1) / chunks;
+}
+
+hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+int check_ctx_len(const cats_ctx* c, int32_t ctx_len) {
+    if (!c) return CATS_EINVAL;
+    if (c->T < 1) return CATS_ESTATE;
+    if (ctx_len < 0) return CATS_EINVAL;
+    if (static_cast<int64_t>(ctx_len) + c->T > c->d.max_ctx) return CATS_ECAPACITY;
+    return CATS_OK;
+}
+
+bool layer_ok(const cats_layer_weights* w) {
+    return w && w->wq && w->wk && w->wv && w->wo && w->w_gate && w->w_up && w->w_down && w->g_attn &&
+           w->g_ffn;
+}
+
+void enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, const void* w2,
+                  int seg_rows, int N, int K, int* splits_out, hipStream_t st) {
+    const SplitPlan p = plan_split(N, K);
+    GemmArgs g;
+    g.x = x;
+    g.w[0] = static_cast<const bf16_t*>(w0);
+    g.w[1] = static_cast<const bf16_t*>(w1 ? w1 : w0);
+    g.w[2] = static_cast<const bf16_t*>(w2 ? w2 : w0);
+    g.seg_rows = seg_rows;
+    g.N = N;
+    g.K = K;
+    g.T = c->T;
+    g.k_per_split = p.k_per_split;
+    g.part = c->part;
+    launch_gemm(g, p.splits, st);
+    *splits_out = p.splits;
+}
+
+void enqueue_attention(cats_ctx* c, const bf16_t* q, const cats_kv_layer* kv, int ctx_len, bf16_t* out,
+                       hipStream_t st) {
+    AttnArgs a;
+    a.q = q;
+    a.kc = static_cast<const bf16_t*>(kv->k);
+    a.vt = static_cast<const bf16_t*>(kv->v);
+    a.parent = c->parent;
+    a.T = c->T;
+    a.H = c->d.hidden;
+    a.nh = c->d.n_heads;
+    a.d = c->d.head_dim;
+    a.max_ctx = c->d.max_ctx;
+    a.ctx_len = ctx_len;
+    const int n_keys = ctx_len + c->T;
+    a.blocks_per_chunk = attn_blocks_per_chunk(c, n_keys);
+    const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
+    a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
+    a.t_pad = (c->T + 31) / 32 * 32;
+    a.po = c->attn_po;
+    a.pml = c->attn_pml;
+    a.out = out;
+    launch_attention(a, st);
+}
+
+// One decoder layer.  On entry c->xn holds rmsnorm(x)*g_attn of this layer; on
+// exit x is updated and, if next_gain is given, c->xn holds rmsnorm(x)*next_gain.
+void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cats_kv_layer* kv,
+                   int ctx_len, const void* next_gain, hipStream_t st) {
+    const int H = c->d.hidden, F = c->d.ffn, T = c->T;
+    int splits = 1;
+    // attention block
+    enqueue_gemm(c, c->xn, w->wq, w->wk, w->wv, H, 3 * H, H, &splits, st);
+    QkvRopeArgs qa;
+    qa.part = c->part;
+    qa.splits = splits;
+    qa.cs = c->rope_cs;
+    qa.q = c->q;
+    qa.kc = static_cast<bf16_t*>(kv->k);
+    qa.vt = static_cast<bf16_t*>(kv->v);
+    qa.T = T;
+    qa.H = H;
+    qa.nh = c->d.n_heads;
+    qa.d = c->d.head_dim;
+    qa.max_ctx = c->d.max_ctx;
+    qa.ctx_len = ctx_len;
+    launch_qkv_rope(qa, st);
+    enqueue_attention(c, c->q, kv, ctx_len, c->attn, st);
+    enqueue_gemm(c, c->attn, w->wo, nullptr, nullptr, H, H, H, &splits, st);
+    ResidualNormArgs rn;
+    rn.x = x;
+    rn.x_in = nullptr;
+    rn.embed = nullptr;
+    rn.token = nullptr;
+    rn.part = c->part;
+    rn.splits = splits;
+    rn.gain = static_cast<const bf16_t*>(w->g_ffn);
+    rn.xn = c->xn;
+    rn.T = T;
+    rn.H = H;
+    rn.eps = c->d.rms_eps;
+    launch_residual_norm(rn, st);
+    // feed-forward block
+    enqueue_gemm(c, c->xn, w->w_gate, w->w_up, nullptr, F, 2 * F, H, &splits, st);
+    SwigluArgs sa;
+    sa.part = c->part;
+    sa.splits = splits;
+    sa.h = c->hact;
+    sa.T = T;
+    sa.F = F;
+    launch_swiglu(sa, st);
+    enqueue_gemm(c, c->hact, w->w_down, nullptr, nullptr, H, H, F, &splits, st);
+    rn.splits = splits;
+    rn.gain = static_cast<const bf16_t*>(next_gain);
+    launch_residual_norm(rn, st);
+}
+
+void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
+    RopeTableArgs r;
+    r.depth = c->depth;
+    r.cs = c->rope_cs;
+    r.T = c->T;
+    r.d = c->d.head_dim;
+    r.ctx_len = ctx_len;
+    r.base = c->d.rope_base;
+    launch_rope_table(r, st);
+}
+
+void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
+                     float* margin_out, hipStream_t st) {
+    int splits = 1;
+    enqueue_gemm(c, c->xn, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, &splits, st);
+    ArgmaxArgs am;
+    am.part = c->part;
+    am.splits = splits;
+    am.T = c->T;
+    am.V = c->d.vocab;
+    am.logits = logits_out;
+    am.amax = argmax_out;
+    am.margin = margin_out;
+    launch_argmax(am, st);
+}
+
+int enqueue_accept_compact(cats_ctx* c, const int32_t* amax, const cats_kv_layer* kv, int layer_begin,
+                           int layer_end, int ctx_len, cats_accept_result* out_dev,
+                           cats_accept_result* out_host, hipStream_t st) {
+    launch_accept(c->token, c->parent, c->depth, amax, c->T, ctx_len, out_dev, st);
+    if (layer_end > layer_begin) {
+        CompactArgs ca;
+        ca.n_layers = layer_end - layer_begin;
+        for (int l = layer_begin; l < layer_end; ++l) {
+            ca.k[l - layer_begin] = static_cast<bf16_t*>(kv[l].k);
+            ca.v[l - layer_begin] = static_cast<bf16_t*>(kv[l].v);
+        }
+        ca.nh = c->d.n_heads;
+        ca.d = c->d.head_dim;
+        ca.max_ctx = c->d.max_ctx;
+        ca.ctx_len = ctx_len;
+        ca.res = out_dev;
+        launch_compact(ca, st);
+    }
+    HIP_TRY(hipGetLastError());
+    if (out_host) {
+        HIP_TRY(hipMemcpyAsync(out_host, out_dev, sizeof(cats_accept_result), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+    }
+    return CATS_OK;
+}
+
+bool kv_ok(const cats_kv_layer* kv, int lb, int le) {
+    if (!kv) return false;
+    for (int l = lb; l < le; ++l)
+        if (!kv[l].k || !kv[l].v) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cats_create(const cats_model_desc* desc, cats_ctx** out) {
+    if (!desc || !out) return CATS_EINVAL;
+    const cats_model_desc& d = *desc;
+    if (d.n_layers < 1 || d.n_layers > CATS_MAX_LAYERS || d.hidden < 64 || d.hidden % 64 != 0 ||
+        d.hidden > 8192 || d.n_heads < 1 || (d.head_dim != 64 && d.head_dim != 128) ||
+        d.n_heads * d.head_dim != d.hidden || d.ffn < 16 || d.ffn % 16 != 0 || d.vocab < 2 ||
+        d.max_ctx < 64 || d.max_ctx % 64 != 0 || d.max_tree < 1 || d.max_tree > CATS_MAX_TREE ||
+        !(d.rms_eps > 0.f) || !(d.rope_base > 1.f))
+        return CATS_EINVAL;
+    cats_ctx* c = new (std::nothrow) cats_ctx();
+    if (!c) return CATS_EHIP;
+    c->d = d;
+    c->T = 0;
+    if (hipGetDevice(&c->device) != hipSuccess) {
+        delete c;
+        return hip_fail(hipGetLastError());
+    }
+    const size_t Tm = d.max_tree, H = d.hidden, F = d.ffn;
+    // split-K partials: the largest splits*N over the five GEMM shapes
+    size_t part_cols = 0;
+    const int shapes[5][2] = {{3 * d.hidden, d.hidden}, {d.hidden, d.hidden}, {2 * d.ffn, d.hidden},
+                              {d.hidden, d.ffn}, {d.vocab, d.hidden}};
+    for (auto& s : shapes)
+        part_cols = std::max(part_cols, static_cast<size_t>(plan_split(s[0], s[1]).splits) * s[0]);
+    c->part_elems = part_cols * Tm;
+    c->attn_max_chunks = 32;
+    const size_t t_pad = (Tm + 31) / 32 * 32;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += align256(bytes);
+        return o;
+    };
+    const size_t o_tok = take(Tm * 4), o_par = take(Tm * 4), o_dep = take(Tm * 4);
+    const size_t o_x = take(Tm * H * 4), o_xn = take(Tm * H * 2), o_q = take(Tm * H * 2);
+    const size_t o_attn = take(Tm * H * 2), o_h = take(Tm * F * 2);
+    const size_t o_part = take(c->part_elems * 4);
+    const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
+    const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
+    const size_t o_pml = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * 2 * 4);
+    const size_t o_amax = take(Tm * 4);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->flat), off);
+    if (e != hipSuccess) {
+        delete c;
+        return hip_fail(e);
+    }
+    e = hipMemset(c->flat, 0, off);
+    if (e != hipSuccess) {
+        (void)hipFree(c->flat);
+        delete c;
+        return hip_fail(e);
+    }
+    char* b = c->flat;
+    c->token = reinterpret_cast<int32_t*>(b + o_tok);
+    c->parent = reinterpret_cast<int32_t*>(b + o_par);
+    c->depth = reinterpret_cast<int32_t*>(b + o_dep);
+    c->x = reinterpret_cast<float*>(b + o_x);
+    c->xn = reinterpret_cast<bf16_t*>(b + o_xn);
+    c->q = reinterpret_cast<bf16_t*>(b + o_q);
+    c->attn = reinterpret_cast<bf16_t*>(b + o_attn);
+    c->hact = reinterpret_cast<bf16_t*>(b + o_h);
+    c->part = reinterpret_cast<float*>(b + o_part);
+    c->rope_cs = reinterpret_cast<float2*>(b + o_cs);
+    c->attn_po = reinterpret_cast<float*>(b + o_po);
+    c->attn_pml = reinterpret_cast<float*>(b + o_pml);
+    c->amax = reinterpret_cast<int32_t*>(b + o_amax);
+    *out = c;
+    return CATS_OK;
+}
+
+int cats_destroy(cats_ctx* ctx) {
+    if (!ctx) return CATS_EINVAL;
+    hipError_t e = hipFree(ctx->flat);
+    delete ctx;
+    return e == hipSuccess ? CATS_OK : hip_fail(e);
+}
+
+int cats_set_tree(cats_ctx* ctx, const cats_tree* tree, void* stream) {
+    if (!ctx || !tree || !tree->token || !tree->parent || !tree->depth) return CATS_EINVAL;
+    const int n = tree->n;
+    if (n < 1 || n > ctx->d.max_tree) return CATS_EINVAL;
+    if (tree->parent[0] != -1 || tree->depth[0] != 0) return CATS_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        if (tree->token[i] < 0 || tree->token[i] >= ctx->d.vocab) return CATS_EINVAL;
+        if (i > 0) {
+            const int p = tree->parent[i];
+            if (p < 0 || p >= i) return CATS_EINVAL;
+            if (tree->depth[i] != tree->depth[p] + 1 || tree->depth[i] > CATS_MAX_DEPTH) return CATS_EINVAL;
+        }
+    }
+    TreeUploadArgs up;
+    std::memset(&up, 0, sizeof up);
+    std::memcpy(up.token, tree->token, sizeof(int32_t) * n);
+    std::memcpy(up.parent, tree->parent, sizeof(int32_t) * n);
+    std::memcpy(up.depth, tree->depth, sizeof(int32_t) * n);
+    launch_tree_upload(up, n, ctx->token, ctx->parent, ctx->depth, as_stream(stream));
+    HIP_TRY(hipGetLastError());
+    std::memcpy(ctx->h_parent, tree->parent, sizeof(int32_t) * n);
+    std::memcpy(ctx->h_depth, tree->depth, sizeof(int32_t) * n);
+    ctx->T = n;
+    return CATS_OK;
+}
+
+int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden, const cats_kv_layer* kv,
+                      int32_t ctx_len, void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (!layer_ok(w) || !hidden || !kv_ok(kv, 0, 1)) return CATS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    enqueue_rope_table(ctx, ctx_len, st);
+    ResidualNormArgs rn;
+    rn.x = hidden;
+    rn.x_in = nullptr;
+    rn.embed = nullptr;
+    rn.token = nullptr;
+    rn.part = nullptr;
+    rn.splits = 0;
+    rn.gain = static_cast<const bf16_t*>(w->g_attn);
+    rn.xn = ctx->xn;
+    rn.T = ctx->T;
+    rn.H = ctx->d.hidden;
+    rn.eps = ctx->d.rms_eps;
+    launch_residual_norm(rn, st);
+    enqueue_layer(ctx, w, hidden, kv, ctx_len, nullptr, st);
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
+int cats_tree_attention(cats_ctx* ctx, const void* q, const cats_kv_layer* kv, int32_t ctx_len, void* out,
+                        void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (!q || !out || !kv_ok(kv, 0, 1)) return CATS_EINVAL;
+    enqueue_attention(ctx, static_cast<const bf16_t*>(q), kv, ctx_len, static_cast<bf16_t*>(out),
+                      as_stream(stream));
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
+int cats_accept_and_compact(cats_ctx* ctx, const int32_t* node_argmax, const cats_kv_layer* kv,
+                            int32_t layer_begin, int32_t layer_end, int32_t ctx_len,
+                            cats_accept_result* out_dev, cats_accept_result* out_host, void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (!node_argmax || !out_dev || layer_begin < 0 || layer_end < layer_begin ||
+        layer_end > ctx->d.n_layers)
+        return CATS_EINVAL;
+    if (layer_end > layer_begin && !kv_ok(kv, layer_begin, layer_end)) return CATS_EINVAL;
+    return enqueue_accept_compact(ctx, node_argmax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host,
+                                  as_stream(stream));
+}
+
+int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final, const void* w_lm,
+                        float* logits_out, int32_t* argmax_out, float* margin_out, void* stream) {
+    if (!ctx) return CATS_EINVAL;
+    if (ctx->T < 1) return CATS_ESTATE;
+    if (!hidden || !g_final || !w_lm || !argmax_out) return CATS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    ResidualNormArgs rn;
+    rn.x = const_cast<float*>(hidden);  // read only: no source/partials given, so nothing is written back
+    rn.x_in = nullptr;
+    rn.embed = nullptr;
+    rn.token = nullptr;
+    rn.part = nullptr;
+    rn.splits = 0;
+    rn.gain = static_cast<const bf16_t*>(g_final);
+    rn.xn = ctx->xn;
+    rn.T = ctx->T;
+    rn.H = ctx->d.hidden;
+    rn.eps = ctx->d.rms_eps;
+    launch_residual_norm(rn, st);
+    enqueue_lm_head(ctx, w_lm, logits_out, argmax_out, margin_out, st);
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
+int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
+                     const void* embed, const float* hidden_in, const void* g_final, const void* w_lm,
+                     const cats_kv_layer* kv, int32_t ctx_len, float* hidden_out, float* logits_out,
+                     int32_t* argmax_out, float* margin_out, cats_accept_result* out_dev,
+                     cats_accept_result* out_host, void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (layer_begin < 0 || layer_end < layer_begin || layer_end > ctx->d.n_layers) return CATS_EINVAL;
+    if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;  // exactly one input source
+    if (!g_final || !w_lm || !out_dev) return CATS_EINVAL;
+    if (layer_end > layer_begin) {
+        if (!layers || !kv_ok(kv, layer_begin, layer_end)) return CATS_EINVAL;
+        for (int l = layer_begin; l < layer_end; ++l)
+            if (!layer_ok(&layers[l])) return CATS_EINVAL;
+    }
+    hipStream_t st = as_stream(stream);
+    const int T = ctx->T, H = ctx->d.hidden;
+    enqueue_rope_table(ctx, ctx_len, st);
+    ResidualNormArgs rn;
+    rn.x = ctx->x;
+    rn.x_in = hidden_in;
+    rn.embed = static_cast<const bf16_t*>(embed);
+    rn.token = ctx->token;
+    rn.part = nullptr;
+    rn.splits = 0;
+    rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : g_final);
+    rn.xn = ctx->xn;
+    rn.T = T;
+    rn.H = H;
+    rn.eps = ctx->d.rms_eps;
+    launch_residual_norm(rn, st);
+    for (int l = layer_begin; l < layer_end; ++l) {
+        const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : g_final;
+        enqueue_layer(ctx, &layers[l], ctx->x, &kv[l], ctx_len, next_gain, st);
+    }
+    if (hidden_out)
+        HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
+    int32_t* amax = argmax_out ? argmax_out : ctx->amax;
+    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
+    HIP_TRY(hipGetLastError());
+    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
+}
+
+const char* cats_gemm_kernel_name(void) { return "cats_gemm_skinny_bf16"; }
+
+const char* cats_strerror(int status) {
+    switch (status) {
+        case CATS_OK: return "ok";
+        case CATS_EINVAL: return "invalid argument (null pointer, bad shape, malformed tree or token out of range)";
+        case CATS_ECAPACITY: return "ctx_len + tree size exceeds max_ctx";
+        case CATS_ESTATE: return "no tree has been set on this context";
+        case CATS_EHIP: return hipGetErrorString(g_last_hip);
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

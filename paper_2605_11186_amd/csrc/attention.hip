@@ -1,0 +1,221 @@
+// Tree-masked attention over the KV cache plus the tree nodes (paper Fig. 4,
+// right-lower: the tree attention mask; Sec. 3.2 "Target verification pass").
+//
+// Node i attends to cache rows [0, ctx_len) and to rows ctx_len + a for every a
+// on its root-to-node path.  The ancestor sets are built inside the kernel from
+// parent[] (staged in LDS) as 128-bit masks.
+//
+// Work split: one wave per (head, chunk of key blocks, group of 32 queries).
+// Scores are computed transposed, S^T = K Q^T, with the 16x16x32 bf16 MFMA, so a
+// lane owns ONE query column and 8 keys of every 32-key block: the running
+// max / sum of the online softmax are per-lane scalars shared by four lanes and
+// reduced with two wave shuffles, and the probabilities are already laid out as
+// the B operand of the second product O^T = V^T P^T.  V is cached transposed
+// ([head][dim][row]) so that its A operand is a plain 128-bit load as well; no
+// LDS round trip for K, V or P.  Chunks are merged afterwards with the usual
+// log-sum-exp rescaling.
+#include "common.hpp"
+
+namespace {
+
+// MFMA 16x16x32 bf16 (wave64): lane l supplies, for A, row l%16 and
+// k = 8*(l/16)..+7; for B, column l%16 and the same k; its 4 results are
+// D[4*(l/16) + r][l%16].
+template <int D>
+__global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
+    constexpr int KS = D / 32;  // k-steps of the score product
+    constexpr int DB = D / 16;  // 16-row blocks of O^T
+    __shared__ int32_t s_parent[CATS_MAX_TREE];
+
+    const int lane = threadIdx.x;
+    const int m = lane & 15, q4 = lane >> 4;
+    const int chunk = blockIdx.x, h = blockIdx.y, qbase = blockIdx.z * 32;
+    const int S = a.ctx_len, T = a.T;
+    const int n_keys = S + T;
+
+    for (int i = lane; i < T; i += 64) s_parent[i] = a.parent[i];
+    __syncthreads();
+
+    // ancestor-or-self masks of this lane's two queries
+    uint32_t anc[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        anc[qb][0] = anc[qb][1] = anc[qb][2] = anc[qb][3] = 0u;
+        int node = qbase + 16 * qb + m;
+        if (node >= T) node = -1;
+        for (int step = 0; step <= CATS_MAX_DEPTH && node >= 0; ++step) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                if ((node >> 5) == w) anc[qb][w] |= 1u << (node & 31);
+            node = s_parent[node];
+        }
+    }
+
+    // Q^T fragments (B operand of the score product): column = query, k = dim
+    bf16x8 qf[2][KS];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int t = qbase + 16 * qb + m;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            u32x4 v = u32x4{0u, 0u, 0u, 0u};
+            if (t < T)
+                v = *reinterpret_cast<const u32x4*>(a.q + static_cast<size_t>(t) * a.H + h * D + 32 * s + 8 * q4);
+            qf[qb][s] = as_bf16x8(v);
+        }
+    }
+
+    f32x4 o[2][DB];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) o[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun[2] = {-1e30f, -1e30f};
+    float lrun[2] = {0.f, 0.f};  // this lane's share of the row sum
+
+    const float scale = rsqrtf(static_cast<float>(D));
+    const bf16_t* kbase = a.kc + static_cast<size_t>(h) * a.max_ctx * D;
+    const bf16_t* vbase = a.vt + static_cast<size_t>(h) * D * a.max_ctx;
+
+    const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
+    const int blk_begin = chunk * a.blocks_per_chunk;
+    const int blk_end = min(n_blocks, blk_begin + a.blocks_per_chunk);
+
+    for (int blk = blk_begin; blk < blk_end; ++blk) {
+        const int j0 = blk * ATTN_KB;
+        // score block rows are permuted so that a lane ends up with 8 consecutive keys:
+        // sub-block b, MFMA row mm  <->  key j0 + 8*(mm/4) + 4*b + mm%4
+        bf16x8 kf[2][KS];
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int key = j0 + 8 * (m >> 2) + 4 * b + (m & 3);
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                kf[b][s] = as_bf16x8(*reinterpret_cast<const u32x4*>(
+                    kbase + static_cast<size_t>(key) * D + 32 * s + 8 * q4));
+        }
+        // V^T fragments: row = dim, k = 8 consecutive keys starting at j0 + 8*q4
+        const int key0 = j0 + 8 * q4;
+        bf16x8 vf[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            u32x4 v = *reinterpret_cast<const u32x4*>(
+                vbase + static_cast<size_t>(16 * db + m) * a.max_ctx + key0);
+            if (key0 + 8 > n_keys) {  // rows past the tree may hold anything: zero them
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (key0 + 2 * e >= n_keys) v[e] &= 0xFFFF0000u;
+                    if (key0 + 2 * e + 1 >= n_keys) v[e] &= 0x0000FFFFu;
+                }
+            }
+            vf[db] = as_bf16x8(v);
+        }
+
+        const bool all_ctx = j0 + ATTN_KB <= S;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            f32x4 st[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                st[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    st[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][s], qf[qb][s], st[b], 0, 0, 0);
+            }
+            // this lane: query column m of group qb, keys key0 + 4*b + r
+            float sc[8];
+            bool vis[8];
+            float bmax = -1e30f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int key = key0 + i;
+                bool v = true;
+                if (!all_ctx) {
+                    const int rel = key - S;
+                    v = rel < 0;
+                    if (rel >= 0 && rel < T) {
+                        uint32_t word = anc[qb][0];
+#pragma unroll
+                        for (int w = 1; w < 4; ++w)
+                            if ((rel >> 5) == w) word = anc[qb][w];
+                        v = (word >> (rel & 31)) & 1u;
+                    }
+                }
+                vis[i] = v;
+                sc[i] = v ? st[i >> 2][i & 3] * scale : -1e30f;
+                bmax = fmaxf(bmax, sc[i]);
+            }
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+            const float mnew = fmaxf(mrun[qb], bmax);
+            const float alpha = __expf(mrun[qb] - mnew);
+            mrun[qb] = mnew;
+            float p[8];
+            float psum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = vis[i] ? __expf(sc[i] - mnew) : 0.f;
+                psum += p[i];
+            }
+            lrun[qb] = lrun[qb] * alpha + psum;
+            const u32x4 pv = {pack_bf2(p[0], p[1]), pack_bf2(p[2], p[3]), pack_bf2(p[4], p[5]),
+                              pack_bf2(p[6], p[7])};
+            const bf16x8 pf = as_bf16x8(pv);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                o[qb][db] *= alpha;
+                o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[qb][db], 0, 0, 0);
+            }
+        }
+    }
+
+    // partial results of this chunk
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        float l = lrun[qb];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int t = qbase + 16 * qb + m;
+        const size_t slot = (static_cast<size_t>(h) * a.n_chunks + chunk) * a.t_pad + t;
+        float* po = a.po + slot * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            *reinterpret_cast<f32x4*>(po + 16 * db + 4 * q4) = o[qb][db];
+        if (q4 == 0) {
+            a.pml[slot * 2] = mrun[qb];
+            a.pml[slot * 2 + 1] = l;
+        }
+    }
+}
+
+// out[t][h*D + dd] = sum_c exp(m_c - M) O_c[dd] / sum_c exp(m_c - M) l_c
+template <int D>
+__global__ void cats_tree_attention_merge(AttnArgs a) {
+    const int t = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
+    float M = -1e30f;
+    for (int c = 0; c < a.n_chunks; ++c) {
+        const size_t slot = (static_cast<size_t>(h) * a.n_chunks + c) * a.t_pad + t;
+        M = fmaxf(M, a.pml[slot * 2]);
+    }
+    float num = 0.f, den = 0.f;
+    for (int c = 0; c < a.n_chunks; ++c) {
+        const size_t slot = (static_cast<size_t>(h) * a.n_chunks + c) * a.t_pad + t;
+        const float wgt = __expf(a.pml[slot * 2] - M);
+        num += wgt * a.po[slot * D + dd];
+        den += wgt * a.pml[slot * 2 + 1];
+    }
+    a.out[static_cast<size_t>(t) * a.H + h * D + dd] = f2bf(num / den);
+}
+
+}  // namespace
+
+void launch_attention(const AttnArgs& a, hipStream_t st) {
+    dim3 grid(a.n_chunks, a.nh, a.t_pad / 32);
+    if (a.d == 128) {
+        hipLaunchKernelGGL(cats_tree_attention_partial<128>, grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_merge<128>, dim3(a.T, a.nh), dim3(128), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(cats_tree_attention_partial<64>, grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_merge<64>, dim3(a.T, a.nh), dim3(64), 0, st, a);
+    }
+}

@@ -1,0 +1,130 @@
+// Shared device helpers and kernel argument blocks of the gfx950 verify library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cats.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// round-to-nearest-even; inputs here are always finite
+__device__ __forceinline__ bf16_t f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return static_cast<bf16_t>(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+    return static_cast<uint32_t>(f2bf(lo)) | (static_cast<uint32_t>(f2bf(hi)) << 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// ---------------------------------------------------------------- GEMM
+// Y[t][n] = sum_k X[t][k] * W[n][k] for t < T, written as float32 partial sums
+// part[split][t][n]; split s covers k in [s*k_per_split, min(K, (s+1)*k_per_split)).
+// W may be given as up to three row segments of seg_rows rows each (q|k|v, gate|up).
+struct GemmArgs {
+    const bf16_t* x;  // [T][K]
+    const bf16_t* w[3];
+    int seg_rows;
+    int N, K, T;
+    int k_per_split;  // multiple of the kernel's K chunk
+    float* part;
+};
+constexpr int GEMM_BN = 128;  // weight rows per workgroup
+constexpr int GEMM_KC = 128;  // k elements per pipeline stage
+void launch_gemm(const GemmArgs& a, int splits, hipStream_t st);
+
+// ---------------------------------------------------------------- row kernels
+struct ResidualNormArgs {
+    float* x;               // [T][H] residual stream, in/out
+    const float* x_in;      // optional [T][H]: start from this instead of x
+    const bf16_t* embed;    // optional [V][H]: start from embed[token[t]]
+    const int32_t* token;   // device [T]
+    const float* part;      // optional [splits][T][H] partial sums to add
+    int splits;
+    const bf16_t* gain;     // optional [H]: if given, xn = rmsnorm(x) * gain
+    bf16_t* xn;             // [T][H]
+    int T, H;
+    float eps;
+};
+void launch_residual_norm(const ResidualNormArgs& a, hipStream_t st);
+
+struct RopeTableArgs {
+    const int32_t* depth;  // device [T]
+    float2* cs;            // [T][d/2] (cos, sin)
+    int T, d, ctx_len;
+    float base;
+};
+void launch_rope_table(const RopeTableArgs& a, hipStream_t st);
+
+struct QkvRopeArgs {
+    const float* part;  // [splits][T][3H]: q | k | v
+    int splits;
+    const float2* cs;   // [T][d/2]
+    bf16_t* q;          // [T][H]
+    bf16_t* kc;         // [nh][max_ctx][d]
+    bf16_t* vt;         // [nh][d][max_ctx]
+    int T, H, nh, d, max_ctx, ctx_len;
+};
+void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
+
+struct SwigluArgs {
+    const float* part;  // [splits][T][2F]: gate | up
+    int splits;
+    bf16_t* h;          // [T][F]
+    int T, F;
+};
+void launch_swiglu(const SwigluArgs& a, hipStream_t st);
+
+struct ArgmaxArgs {
+    const float* part;  // [splits][T][V]
+    int splits;
+    int T, V;
+    float* logits;      // optional [T][V]
+    int32_t* amax;      // [T]
+    float* margin;      // optional [T]
+};
+void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
+
+// ---------------------------------------------------------------- attention
+struct AttnArgs {
+    const bf16_t* q;        // [T][H]
+    const bf16_t* kc;       // [nh][max_ctx][d]
+    const bf16_t* vt;       // [nh][d][max_ctx]
+    const int32_t* parent;  // device [T]
+    int T, H, nh, d, max_ctx, ctx_len;
+    int blocks_per_chunk, n_chunks, t_pad;
+    float* po;              // [nh][n_chunks][t_pad][d]
+    float* pml;             // [nh][n_chunks][t_pad][2]
+    bf16_t* out;            // [T][H]
+};
+constexpr int ATTN_KB = 32;  // keys per block
+void launch_attention(const AttnArgs& a, hipStream_t st);
+
+// ---------------------------------------------------------------- accept / compact
+struct TreeUploadArgs {
+    int32_t token[CATS_MAX_TREE], parent[CATS_MAX_TREE], depth[CATS_MAX_TREE];
+};
+void launch_tree_upload(const TreeUploadArgs& a, int n, int32_t* token, int32_t* parent,
+                        int32_t* depth, hipStream_t st);
+
+void launch_accept(const int32_t* token, const int32_t* parent, const int32_t* depth,
+                   const int32_t* amax, int T, int ctx_len, cats_accept_result* out,
+                   hipStream_t st);
+
+struct CompactArgs {
+    bf16_t* k[CATS_MAX_LAYERS];
+    bf16_t* v[CATS_MAX_LAYERS];
+    int n_layers;  // entries used
+    int nh, d, max_ctx, ctx_len;
+    const cats_accept_result* res;
+};
+void launch_compact(const CompactArgs& a, hipStream_t st);

@@ -1,0 +1,184 @@
+// Small per-row kernels around the weight-streaming GEMMs of one decoder layer
+// (the layer internals are those of the LLaMA-family targets the paper
+// evaluates: RMSNorm, rotary embedding, SwiGLU).  Each one also adds up the
+// GEMM's split-K partial sums in a fixed order, so results do not depend on
+// scheduling.
+#include "common.hpp"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// x[t] <- (x_in[t] | embed[token[t]] | x[t]) + sum_s part[s][t];  xn[t] = rmsnorm(x[t]) * gain
+// One workgroup per row.
+constexpr int RN_THREADS = 256;
+constexpr int RN_MAX_PER_THREAD = 32;
+__global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNormArgs a) {
+    __shared__ float red[RN_THREADS / 64];
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x;
+    float v[RN_MAX_PER_THREAD];
+    float ss = 0.f;
+    const size_t row = static_cast<size_t>(t) * a.H;
+    const bf16_t* erow = a.embed ? a.embed + static_cast<size_t>(a.token[t]) * a.H : nullptr;
+#pragma unroll
+    for (int i = 0; i < RN_MAX_PER_THREAD; ++i) {
+        const int j = tid + i * RN_THREADS;
+        if (j < a.H) {
+            float val = erow ? bf2f(erow[j]) : (a.x_in ? a.x_in[row + j] : a.x[row + j]);
+            for (int s = 0; s < a.splits; ++s)
+                val += a.part[(static_cast<size_t>(s) * a.T + t) * a.H + j];
+            v[i] = val;
+            ss += val * val;
+            if (erow || a.x_in || a.splits > 0) a.x[row + j] = val;
+        }
+    }
+    if (!a.gain) return;
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < RN_THREADS / 64; ++w) tot += red[w];
+    const float scale = 1.0f / sqrtf(tot / static_cast<float>(a.H) + a.eps);
+#pragma unroll
+    for (int i = 0; i < RN_MAX_PER_THREAD; ++i) {
+        const int j = tid + i * RN_THREADS;
+        if (j < a.H) a.xn[row + j] = f2bf(v[i] * scale * bf2f(a.gain[j]));
+    }
+}
+
+// cos/sin of pos * base^(-2j/d) for pos = ctx_len + depth[t]; computed in double so
+// that the angle carries no float rounding of a four-digit position.
+__global__ void cats_rope_table(RopeTableArgs a) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int half = a.d / 2;
+    if (idx >= a.T * half) return;
+    const int t = idx / half, j = idx - t * half;
+    const double inv_freq = pow(static_cast<double>(a.base), -2.0 * j / a.d);
+    const double ang = static_cast<double>(a.ctx_len + a.depth[t]) * inv_freq;
+    a.cs[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
+}
+
+// Adds up q|k|v partials, rotates q and k (pairs j, j+d/2), writes q, appends the
+// key row and the (transposed) value column of every node at cache row ctx_len + t.
+// grid (T, nh), block d/2.
+__global__ void cats_qkv_rope_append(QkvRopeArgs a) {
+    const int t = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+    const int half = a.d / 2;
+    const int N = 3 * a.H;
+    float v6[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.splits; ++s) {
+        const float* p = a.part + (static_cast<size_t>(s) * a.T + t) * N + h * a.d + j;
+        v6[0] += p[0];
+        v6[1] += p[half];
+        v6[2] += p[a.H];
+        v6[3] += p[a.H + half];
+        v6[4] += p[2 * a.H];
+        v6[5] += p[2 * a.H + half];
+    }
+    const float2 cs = a.cs[t * half + j];
+    const float q0 = v6[0] * cs.x - v6[1] * cs.y, q1 = v6[0] * cs.y + v6[1] * cs.x;
+    const float k0 = v6[2] * cs.x - v6[3] * cs.y, k1 = v6[2] * cs.y + v6[3] * cs.x;
+    bf16_t* q = a.q + static_cast<size_t>(t) * a.H + h * a.d;
+    q[j] = f2bf(q0);
+    q[j + half] = f2bf(q1);
+    const int row = a.ctx_len + t;
+    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + row) * a.d;
+    k[j] = f2bf(k0);
+    k[j + half] = f2bf(k1);
+    bf16_t* vt = a.vt + static_cast<size_t>(h) * a.d * a.max_ctx + row;
+    vt[static_cast<size_t>(j) * a.max_ctx] = f2bf(v6[4]);
+    vt[static_cast<size_t>(j + half) * a.max_ctx] = f2bf(v6[5]);
+}
+
+// h[t][n] = silu(gate[t][n]) * up[t][n]
+__global__ void cats_swiglu(SwigluArgs a) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= a.T * a.F) return;
+    const int t = idx / a.F, n = idx - t * a.F;
+    float gt = 0.f, up = 0.f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float* p = a.part + (static_cast<size_t>(s) * a.T + t) * (2 * a.F) + n;
+        gt += p[0];
+        up += p[a.F];
+    }
+    a.h[idx] = f2bf(gt / (1.0f + __expf(-gt)) * up);
+}
+
+// Per node: add up the logits partials, optionally store them, find the largest
+// (lowest index on ties) and the runner-up value.  One workgroup per node.
+constexpr int AM_THREADS = 1024;
+__global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
+    __shared__ float s_best[AM_THREADS / 64], s_second[AM_THREADS / 64];
+    __shared__ int s_idx[AM_THREADS / 64];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    float best = -INFINITY, second = -INFINITY;
+    int bidx = 0x7fffffff;
+    for (int v = tid; v < a.V; v += AM_THREADS) {
+        float val = 0.f;
+        for (int s = 0; s < a.splits; ++s) val += a.part[(static_cast<size_t>(s) * a.T + t) * a.V + v];
+        if (a.logits) a.logits[static_cast<size_t>(t) * a.V + v] = val;
+        if (val > best) {  // indices ascend within a thread: strict > keeps the lowest
+            second = best;
+            best = val;
+            bidx = v;
+        } else if (val > second) {
+            second = val;
+        }
+    }
+    auto merge = [](float& b, int& bi, float& s2, float ob, int oi, float os) {
+        if (ob > b || (ob == b && oi < bi)) {
+            s2 = fmaxf(fmaxf(s2, os), b);
+            b = ob;
+            bi = oi;
+        } else {
+            s2 = fmaxf(s2, ob);
+        }
+    };
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o), os = __shfl_xor(second, o);
+        const int oi = __shfl_xor(bidx, o);
+        merge(best, bidx, second, ob, oi, os);
+    }
+    if ((tid & 63) == 0) {
+        s_best[tid >> 6] = best;
+        s_second[tid >> 6] = second;
+        s_idx[tid >> 6] = bidx;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < AM_THREADS / 64; ++w) merge(best, bidx, second, s_best[w], s_idx[w], s_second[w]);
+        a.amax[t] = bidx;
+        if (a.margin) a.margin[t] = best - second;
+    }
+}
+
+}  // namespace
+
+void launch_residual_norm(const ResidualNormArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(cats_residual_rmsnorm, dim3(a.T), dim3(RN_THREADS), 0, st, a);
+}
+
+void launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
+    const int n = a.T * (a.d / 2);
+    hipLaunchKernelGGL(cats_rope_table, dim3((n + 255) / 256), dim3(256), 0, st, a);
+}
+
+void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T, a.nh), dim3(a.d / 2), 0, st, a);
+}
+
+void launch_swiglu(const SwigluArgs& a, hipStream_t st) {
+    const int n = a.T * a.F;
+    hipLaunchKernelGGL(cats_swiglu, dim3((n + 255) / 256), dim3(256), 0, st, a);
+}
+
+void launch_argmax(const ArgmaxArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(cats_argmax, dim3(a.T), dim3(AM_THREADS), 0, st, a);
+}
