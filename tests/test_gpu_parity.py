@@ -166,7 +166,7 @@ def test_single_layer_call_matches_oracle(tiny):
         assert rel_err(gk, kc[l, :S + T]) <= REL_TOL and rel_err(gv, vc[l, :S + T]) <= REL_TOL
 
 
-@pytest.mark.parametrize("S,T", [(0, 1), (5, 3), (128, 15), (200, 128), (95, 64)])
+@pytest.mark.parametrize("S,T", [(0, 1), (5, 3), (128, 15), (190, 128), (95, 64)])
 def test_tree_attention_alone(tiny, S, T):
     d = synth.TINY
     parent, depth = synth.random_tree(T, 8, S + T)
