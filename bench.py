@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the draft-tree verification step on one MI355X.
+
+A "step" is one pass of the whole hot path: tree ingest, embedding rows, every
+decoder layer (weights streamed once for all T tree nodes, tree-masked
+attention), final norm + LM head + per-node argmax, greedy acceptance and KV
+roll-back.  Inputs are seeded and synthetic and already resident in HBM when the
+timed region starts.
+
+Prints ONE JSON line: verify steps/s, the HBM roofline of the dominant
+(weight-streaming GEMM) kernel measured with HIP events, and the CPU oracle
+timed on this machine's host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+WORKLOADS = {
+    # BASELINE configs[1]: Vicuna-7B-shaped single verify step
+    "7b_t63_s1024": dict(model="V7B", ctx=1024, tree="topk63", label="Vicuna-7B-shaped (32L, H4096, F11008, V32000) verify step, 63-node top-k tree (4/3/2/2/1/1 pruned), KV context 1024"),
+    "7b_t64_s1024": dict(model="V7B", ctx=1024, tree="rand64", label="7B-shape, 64-node random tree (depth<=8), KV context 1024"),
+    "13b_t64_s2048": dict(model="V13B", ctx=2048, tree="rand64d7", label="13B-shape (40L, H5120, F13824), 64-node tree (depth 7), KV context 2048"),
+    "tiny": dict(model="TINY", ctx=128, tree="binary15", label="tiny oracle-check model, 15-node binary tree, KV context 128"),
+}
+
+
+def make_tree(kind, synth):
+    if kind == "topk63":
+        p, d, _ = synth.product_tree_pruned()
+        return p, d
+    if kind == "binary15":
+        return synth.complete_binary_tree(3)
+    if kind == "rand64":
+        return synth.random_tree(64, 8, 1)
+    if kind == "rand64d7":
+        return synth.random_tree(64, 7, 1)
+    if kind.startswith("rand"):
+        return synth.random_tree(int(kind[4:]), 8, 1)
+    raise ValueError(kind)
+
+
+def algorithmic_bytes(dims, T, S, n_layers):
+    """Bytes the method must move per step: every weight once (2 B each), K and V of
+    context + tree once per layer.  Small activations are ignored (< 1 %)."""
+    w_layers = n_layers * dims.layer_weight_elems() * 2
+    w_lm = dims.vocab * dims.hidden * 2
+    kv = n_layers * 2 * (S + T) * dims.hidden * 2
+    return w_layers + w_lm, kv
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="7b_t63_s1024", choices=sorted(WORKLOADS))
+    ap.add_argument("--tree-nodes", type=int, default=0, help="override: random tree with this many nodes")
+    ap.add_argument("--ctx", type=int, default=0, help="override the KV context length")
+    ap.add_argument("--seed", type=int, default=11186)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                 "run it with --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2605_11186_amd as cats
+    import synth
+
+    wl = dict(WORKLOADS[args.workload])
+    dims = getattr(synth, wl["model"])
+    S = args.ctx or wl["ctx"]
+    if args.tree_nodes:
+        parent, depth = synth.random_tree(args.tree_nodes, 8, 1)
+        wl["label"] += f" [override: {args.tree_nodes}-node random tree]"
+    else:
+        parent, depth = make_tree(wl["tree"], synth)
+    if args.ctx:
+        wl["label"] += f" [override: KV context {S}]"
+    T = len(parent)
+    L = dims.n_layers
+    seed = args.seed
+    max_ctx = (S + T + 63) // 64 * 64
+    tok = synth.distinct_sibling_tokens(parent, dims.vocab, seed)
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    t0 = time.time()
+    host_layers = []   # kept only for the CPU-baseline sample
+    d_layers = []
+    n_keep = 0 if args.no_cpu_baseline else min(args.cpu_sample_layers, L)
+    for l in range(L):
+        w = synth.layer_weights(dims, seed, l)
+        d_layers.append({k: to_dev(v) for k, v in w.items()})
+        if l < n_keep:
+            host_layers.append(w)
+    final = synth.final_weights(dims, seed)
+    embed = synth.embedding(dims, seed)
+    d_final = {k: to_dev(v) for k, v in final.items()}
+    d_embed = to_dev(embed)
+    ks, vs, host_kv = [], [], []
+    for l in range(L):
+        k_rows, v_rows = synth.random_kv_context(dims, seed, l, S)
+        k, v = cats.kv_from_rows(to_dev(k_rows), to_dev(v_rows), dims.n_heads, dims.head_dim, max_ctx)
+        ks.append(k)
+        vs.append(v)
+        if l < n_keep:
+            host_kv.append((k_rows, v_rows))
+    gen_s = time.time() - t0
+
+    desc = cats.ModelDesc(L, dims.hidden, dims.n_heads, dims.head_dim, dims.ffn, dims.vocab, max_ctx,
+                          max(T, 1), dims.rms_eps, dims.rope_base)
+    ctx = cats.cats_create(desc)
+    layers_arr = cats.layer_array(d_layers)
+    kv_arr = cats.kv_array(ks, vs)
+    res_dev = cats.accept_result_tensor(dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        cats.cats_set_tree(ctx, tok, parent, depth, stream)
+        cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"], d_final["w_lm"],
+                              kv_arr, S, res_dev, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    accepted = cats.accept_result_from_tensor(res_dev)
+
+    # Same K steps again with HIP events around every GEMM launch (on the launch stream): the
+    # dominant kernel's average duration.  Kept out of the region above so that the event
+    # records do not inflate `value`.
+    cats.cats_profile_gemm(ctx, True)
+    gemm_ms, gemm_launches = 0.0, 0
+    for _ in range(args.steps):
+        step()
+        ms, n = cats.cats_profile_gemm_read(ctx)
+        gemm_ms += ms
+        gemm_launches += n
+    cats.cats_profile_gemm(ctx, False)
+    torch.cuda.synchronize()
+
+    w_bytes, kv_bytes = algorithmic_bytes(dims, T, S, L)
+    gemm_bytes_per_launch = w_bytes * args.steps / gemm_launches
+    gemm_avg_s = gemm_ms * 1e-3 / gemm_launches
+    gemm_gbs = gemm_bytes_per_launch / gemm_avg_s / 1e9
+    step_gbs = (w_bytes + kv_bytes) / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "tree-verify steps/sec",
+        "value": round(1e3 / ms_per_step, 3),
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl["label"], "key": args.workload, "tree_nodes": T, "ctx_len": S,
+                   "layers": L, "seed": seed, "accepted_per_step": accepted["n_accepted"]},
+        "step_hbm": {"algorithmic_bytes": w_bytes + kv_bytes, "weight_bytes": w_bytes, "kv_bytes": kv_bytes,
+                     "achieved_gbs": round(step_gbs, 1), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
+        "roofline": {"bound": "hbm", "kernel": cats.cats_gemm_kernel_name(),
+                     "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "launches_per_step": gemm_launches // args.steps,
+                     "avg_launch_us": round(gemm_avg_s * 1e6, 2),
+                     "bytes_per_launch": int(gemm_bytes_per_launch)},
+        "input_generation_s": round(gen_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle.cats_oracle import Oracle
+        orc = Oracle(dims, host_layers + [None] * (L - n_keep), final, embed, precision="f32")
+        kc, vc = orc.new_cache(max_ctx)
+        for l in range(n_keep):
+            kc[l, :S] = synth.f32_from_bf16_bits(host_kv[l][0])
+            vc[l, :S] = synth.f32_from_bf16_bits(host_kv[l][1])
+        t1 = time.perf_counter()
+        x = orc.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=n_keep)
+        t_layers = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        orc.lm_head(x)
+        t_lm = time.perf_counter() - t1
+        est = t_layers * L / n_keep + t_lm
+        out["cpu_baseline"] = {
+            "value": round(1.0 / est, 5), "unit": "steps/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"float32 oracle, same tree and context: layers 0..{n_keep - 1} of {L} timed "
+                      f"({t_layers:.2f} s) and scaled by {L}/{n_keep}, plus the full LM head ({t_lm:.2f} s)",
+            "est_s_per_step": round(est, 2)}
+
+    cats.cats_destroy(ctx)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

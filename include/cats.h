@@ -152,6 +152,15 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
 int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, const void *g_final, const void *w_lm,
                         float *logits_out, int32_t *argmax_out, float *margin_out, void *stream);
 
+/* Measurement aid for the weight-streaming GEMM (the layer-weight pass of the
+ * "Target verification pass"): while enabled, every GEMM launch made through
+ * this context is bracketed by HIP events on its own stream (at most 1024
+ * launches between two reads).  cats_profile_gemm_read waits for them and
+ * returns the summed kernel time in milliseconds and the launch count (HOST
+ * outputs), then starts a new collection. */
+int cats_profile_gemm(cats_ctx *ctx, int enable);
+int cats_profile_gemm_read(cats_ctx *ctx, float *total_ms, int32_t *launches);
+
 /* Name of the dominant (weight-streaming) kernel as it appears in profiler
  * output, and the text of a status code.  HOST strings, never freed. */
 const char *cats_gemm_kernel_name(void);

@@ -15,7 +15,8 @@ __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWe
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
            "cats_accept_and_compact", "cats_verify_tree", "cats_lm_head_argmax",
-           "cats_gemm_kernel_name", "cats_strerror", "layer_weights_struct", "kv_array",
+           "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
+           "layer_weights_struct", "kv_array",
            "layer_array", "kv_from_rows", "kv_to_rows", "accept_result_tensor",
            "accept_result_from_tensor", "CATS_OK", "CATS_EINVAL", "CATS_ECAPACITY", "CATS_ESTATE",
            "CATS_EHIP"]
@@ -78,6 +79,8 @@ _SIGNATURES = {
     "cats_verify_tree": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_profile_gemm": [C.c_void_p, C.c_int],
+    "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_void_p, C.c_void_p],
 }
@@ -201,6 +204,17 @@ def cats_lm_head_argmax(ctx, hidden, g_final, w_lm, argmax_out, logits_out=None,
                         stream=None):
     _check(library().cats_lm_head_argmax(ctx, _dp(hidden), _dp(g_final), _dp(w_lm), _dp(logits_out),
                                          _dp(argmax_out), _dp(margin_out), _stream(stream)))
+
+
+def cats_profile_gemm(ctx, enable: bool):
+    _check(library().cats_profile_gemm(ctx, int(bool(enable))))
+
+
+def cats_profile_gemm_read(ctx):
+    """(summed GEMM kernel milliseconds, launches) since the last read."""
+    ms, n = C.c_float(), C.c_int32()
+    _check(library().cats_profile_gemm_read(ctx, C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 # ---------------------------------------------------------------- marshalling helpers

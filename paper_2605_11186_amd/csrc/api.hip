@@ -8,6 +8,8 @@
 
 #include "common.hpp"
 
+constexpr int CATS_PROF_MAX = 1024;  // GEMM launches that can be timed between two reads
+
 struct cats_ctx {
     cats_model_desc d;
     int device;
@@ -29,6 +31,10 @@ struct cats_ctx {
     int attn_max_chunks;
     int32_t* amax;   // [max_tree]
     char* flat;      // the single allocation behind all of the above
+    // optional timing of the weight-streaming GEMM launches (measurement aid)
+    bool prof_on;
+    int prof_n;
+    hipEvent_t prof_ev[2 * CATS_PROF_MAX];
 };
 
 namespace {
@@ -111,7 +117,13 @@ void enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, 
     g.T = c->T;
     g.k_per_split = p.k_per_split;
     g.part = c->part;
+    const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
+    if (timed) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], st);
     launch_gemm(g, p.splits, st);
+    if (timed) {
+        (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st);
+        ++c->prof_n;
+    }
     *splits_out = p.splits;
 }
 
@@ -267,6 +279,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     if (!c) return CATS_EHIP;
     c->d = d;
     c->T = 0;
+    c->prof_on = false;
+    c->prof_n = 0;
+    for (auto& e : c->prof_ev) e = nullptr;
     if (hipGetDevice(&c->device) != hipSuccess) {
         delete c;
         return hip_fail(hipGetLastError());
@@ -326,6 +341,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
 
 int cats_destroy(cats_ctx* ctx) {
     if (!ctx) return CATS_EINVAL;
+    for (auto& ev : ctx->prof_ev)
+        if (ev) (void)hipEventDestroy(ev);
     hipError_t e = hipFree(ctx->flat);
     delete ctx;
     return e == hipSuccess ? CATS_OK : hip_fail(e);
@@ -471,6 +488,30 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
     HIP_TRY(hipGetLastError());
     return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
+}
+
+int cats_profile_gemm(cats_ctx* ctx, int enable) {
+    if (!ctx) return CATS_EINVAL;
+    if (enable && !ctx->prof_ev[0])
+        for (auto& ev : ctx->prof_ev) HIP_TRY(hipEventCreate(&ev));
+    ctx->prof_on = enable != 0;
+    ctx->prof_n = 0;
+    return CATS_OK;
+}
+
+int cats_profile_gemm_read(cats_ctx* ctx, float* total_ms, int32_t* launches) {
+    if (!ctx || !total_ms || !launches) return CATS_EINVAL;
+    float sum = 0.f;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        HIP_TRY(hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = ctx->prof_n;
+    ctx->prof_n = 0;
+    return CATS_OK;
 }
 
 const char* cats_gemm_kernel_name(void) { return "cats_gemm_skinny_bf16"; }
