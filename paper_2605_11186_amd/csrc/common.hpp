@@ -38,8 +38,19 @@ struct GemmArgs {
     int k_per_split;  // multiple of the kernel's K chunk
     float* part;
 };
-constexpr int GEMM_BN = 128;  // weight rows per workgroup
-constexpr int GEMM_KC = 128;  // k elements per pipeline stage
+#ifndef CATS_GEMM_BN
+#define CATS_GEMM_BN 256
+#endif
+#ifndef CATS_GEMM_ST
+#define CATS_GEMM_ST 3
+#endif
+#ifndef CATS_GEMM_ST4
+#define CATS_GEMM_ST4 2
+#endif
+constexpr int GEMM_BN = CATS_GEMM_BN;    // weight rows per workgroup (32 per wave)
+constexpr int GEMM_KC = 128;             // k elements per pipeline stage
+constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
+constexpr int GEMM_ST4 = CATS_GEMM_ST4;  // ... for T > 64 (larger accumulators)
 void launch_gemm(const GemmArgs& a, int splits, hipStream_t st);
 
 // ---------------------------------------------------------------- row kernels

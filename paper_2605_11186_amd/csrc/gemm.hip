@@ -5,58 +5,87 @@
 // Y[t][n] = sum_k X[t][k] W[n][k], T <= 128 rows, N and K large.  Every weight
 // element is loaded from HBM exactly once, straight into the MFMA B-operand
 // registers by 128-bit loads; the T activations of the current K chunk are
-// staged in LDS and reused by the four waves of the workgroup.  Each wave owns
-// 32 weight rows, the workgroup 128; the K range is cut into `splits` slices
-// (grid.y) so that enough workgroups exist to fill 256 CUs, and the float32
-// partial sums go to part[split][t][n] for the following epilogue kernel to
-// add up in a fixed order.
+// staged in LDS and shared by all waves of the workgroup.  Each wave owns 32
+// weight rows.  The kernel is bound by HBM latency x bandwidth, so each wave keeps
+// a ring of ST-1 future K chunks (8 KB of weights each) in flight in registers.
+// The K range is cut into `splits` slices (grid.y) so that enough workgroups
+// exist to fill 256 CUs; the float32 partial sums go to part[split][t][n] and the
+// following epilogue kernel adds them up in a fixed order.
 #include "common.hpp"
 
 namespace {
 
 constexpr int XS_ROW = GEMM_KC / 8 + 1;  // u32x4 per staged row: 256 B of data + 16 B pad
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait
+// for every outstanding global load (vmcnt(0)), i.e. drain the prefetch ring.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // MFMA 32x32x16 bf16 operand layout (wave64): lane l supplies, for A, row l%32
 // and k = 8*(l/32)..+7; for B, column l%32 and the same k; the 16 results of a
 // lane are D[8*(r/4) + 4*(l/32) + r%4][l%32].
-template <int TB>
-__global__ __launch_bounds__(256) void cats_gemm_skinny_bf16(GemmArgs a) {
-    __shared__ u32x4 xs[2][TB * 32][XS_ROW];
+//
+// TB: 32-row blocks of X (T <= 32*TB).  NW: waves per workgroup.  ST: ring depth.
+template <int TB, int NW, int ST>
+__global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
+    constexpr int THREADS = 64 * NW;
+    constexpr int XPT = TB * 512 / THREADS;       // u32x4 of the X tile per thread
+    constexpr int XROWS_PER_PASS = THREADS / 16;  // tile rows covered by one pass of the block
+    constexpr int NBUF = (ST % 2 == 0) ? 2 : ST;  // LDS buffers; the index is static under unrolling
+    __shared__ u32x4 xs[NBUF][TB * 32][XS_ROW];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
 
-    const int n = blockIdx.x * GEMM_BN + wave * 32 + col;
+    const int n = blockIdx.x * (32 * NW) + wave * 32 + col;
     const bool n_ok = n < a.N;
     const int nn = n_ok ? n : a.N - 1;
     const int seg = nn / a.seg_rows;
     const bf16_t* wseg = seg == 0 ? a.w[0] : (seg == 1 ? a.w[1] : a.w[2]);
-    const bf16_t* wrow = wseg + static_cast<size_t>(nn - seg * a.seg_rows) * a.K;
+    const bf16_t* wrow = wseg + static_cast<size_t>(nn - seg * a.seg_rows) * a.K + 8 * g;
 
     const int k_begin = blockIdx.y * a.k_per_split;
     const int k_end = min(a.K, k_begin + a.k_per_split);
     const int n_chunks = (k_end - k_begin + GEMM_KC - 1) / GEMM_KC;
+#define CATS_CHUNK_K(c) (k_begin + (c) * GEMM_KC)
 
     // staging assignment: thread -> (row, 16-byte column) of the X tile
     const int xr = tid >> 4, xc = tid & 15;
 
-    u32x4 wreg[8];
-    u32x4 xreg[TB * 2];
+    u32x4 wst[ST][8];
+    u32x4 xst[ST][XPT];
     const u32x4 zero4 = u32x4{0u, 0u, 0u, 0u};
 
-#define CATS_LOAD_W(k0)                                                                     \
-    _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                         \
-        const int kk = (k0) + 16 * j + 8 * g;                                               \
-        wreg[j] = kk < k_end ? *reinterpret_cast<const u32x4*>(wrow + kk) : zero4;          \
+    // The scheduling barriers keep the chunks' loads in issue order (the compiler would
+    // otherwise interleave them freely and then has to wait for the youngest one).
+    // Loads are unconditional (clamped addresses) so that the pipeline is straight-line code:
+    // a predicated load would put every load in its own basic block and the compiler would
+    // then wait for ALL outstanding loads at each use.  Out-of-range X entries are zeroed by
+    // a select; the matching W values are finite and get multiplied by those zeros.
+    bool x_row_ok[XPT];
+    const bf16_t* x_ptr[XPT];
+#pragma unroll
+    for (int p = 0; p < XPT; ++p) {
+        const int r = xr + XROWS_PER_PASS * p;
+        x_row_ok[p] = r < a.T;
+        x_ptr[p] = a.x + static_cast<size_t>(min(r, a.T - 1)) * a.K;
     }
-#define CATS_LOAD_X(k0)                                                                     \
-    _Pragma("unroll") for (int p = 0; p < TB * 2; ++p) {                                    \
-        const int r = xr + 16 * p;                                                          \
-        const int kk = (k0) + 8 * xc;                                                       \
-        xreg[p] = (r < a.T && kk < k_end)                                                   \
-                      ? *reinterpret_cast<const u32x4*>(a.x + static_cast<size_t>(r) * a.K + kk) \
-                      : zero4;                                                              \
+    const int k_last_x = a.K - 8, k_last_w = a.K - 16;
+#define CATS_LOAD_CHUNK(slot, k0)                                                                   \
+    {                                                                                               \
+        const int k0_ = (k0);                                                                       \
+        const int kx = k0_ + 8 * xc;                                                                \
+        _Pragma("unroll") for (int p = 0; p < XPT; ++p)                                             \
+            xst[slot][p] = *reinterpret_cast<const u32x4*>(x_ptr[p] + min(kx, k_last_x));           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
+            wst[slot][j] = *reinterpret_cast<const u32x4*>(wrow + min(k0_ + 16 * j, k_last_w));     \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
     f32x16 acc[TB];
@@ -65,34 +94,55 @@ __global__ __launch_bounds__(256) void cats_gemm_skinny_bf16(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
 
-    if (n_chunks > 0) {
-        CATS_LOAD_W(k_begin)
-        CATS_LOAD_X(k_begin)
+    // prologue: chunks 0 .. ST-2 in flight
+#pragma unroll
+    for (int s = 0; s < ST - 1; ++s) CATS_LOAD_CHUNK(s, CATS_CHUNK_K(s))
+
+    // One pipeline step: stage X of chunk c (ring slot s) in LDS, optionally refill the slot
+    // freed by the previous step with chunk c+ST-1, multiply.
+#define CATS_STEP(s, c, REFILL)                                                                     \
+    {                                                                                               \
+        constexpr int buf = (s) % NBUF;                                                             \
+        _Pragma("unroll") for (int p = 0; p < XPT; ++p) /* zero what lies outside the tile */       \
+            xs[buf][xr + XROWS_PER_PASS * p][xc] =                                                  \
+                (x_row_ok[p] && CATS_CHUNK_K(c) + 8 * xc < k_end) ? xst[s][p] : zero4;      \
+        lds_barrier();                                                                              \
+        if (REFILL) CATS_LOAD_CHUNK(((s) + ST - 1) % ST, CATS_CHUNK_K((c) + ST - 1))        \
+        _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
+            const bf16x8 b = as_bf16x8(wst[s][j]);                                                  \
+            _Pragma("unroll") for (int tb = 0; tb < TB; ++tb) {                                     \
+                const bf16x8 av = as_bf16x8(xs[buf][tb * 32 + col][2 * j + g]);                     \
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc[tb], 0, 0, 0);         \
+            }                                                                                       \
+        }                                                                                           \
     }
-    int buf = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-#pragma unroll
-        for (int p = 0; p < TB * 2; ++p) xs[buf][xr + 16 * p][xc] = xreg[p];
-        __syncthreads();
-        u32x4 wcur[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) wcur[j] = wreg[j];
-        if (c + 1 < n_chunks) {
-            const int k0 = k_begin + (c + 1) * GEMM_KC;
-            CATS_LOAD_W(k0)
-            CATS_LOAD_X(k0)
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bf16x8 b = as_bf16x8(wcur[j]);
-#pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                const bf16x8 av = as_bf16x8(xs[buf][tb * 32 + col][2 * j + g]);
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc[tb], 0, 0, 0);
+
+    // Full groups of ST chunks run without any inner condition: a conditional step inside
+    // the loop would give the compiler a (never taken) path on which ring loads stay
+    // unconsumed, and it would then drain all loads at the loop head.
+    static_assert(ST >= 2 && ST <= 4, "ring depth");
+    int c0 = 0;
+    for (; c0 + ST <= n_chunks; c0 += ST) {
+        CATS_STEP(0, c0, true)
+        CATS_STEP(1, c0 + 1, true)
+        if constexpr (ST > 2) CATS_STEP(2, c0 + 2, true)
+        if constexpr (ST > 3) CATS_STEP(3, c0 + 3, true)
+    }
+    // tail: fewer than ST chunks left, already in flight
+    if (c0 < n_chunks) {
+        CATS_STEP(0, c0, false)
+        if (c0 + 1 < n_chunks) {
+            CATS_STEP(1, c0 + 1, false)
+            if constexpr (ST > 3) {
+                if (c0 + 2 < n_chunks) CATS_STEP(2, c0 + 2, false)
+            } else if constexpr (ST > 2) {
+                if (c0 + 2 < n_chunks) CATS_STEP(2, c0 + 2, false)
             }
         }
-        buf ^= 1;
     }
+#undef CATS_STEP
+#undef CATS_CHUNK_K
+#undef CATS_LOAD_CHUNK
 
     if (n_ok) {
         float* out = a.part + static_cast<size_t>(blockIdx.y) * a.T * a.N + n;
@@ -109,12 +159,13 @@ __global__ __launch_bounds__(256) void cats_gemm_skinny_bf16(GemmArgs a) {
 }  // namespace
 
 void launch_gemm(const GemmArgs& a, int splits, hipStream_t st) {
+    constexpr int NW = GEMM_BN / 32;
     dim3 grid((a.N + GEMM_BN - 1) / GEMM_BN, splits);
     const int tb = (a.T + 31) / 32;
     switch (tb) {
-        case 1: hipLaunchKernelGGL(cats_gemm_skinny_bf16<1>, grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL(cats_gemm_skinny_bf16<2>, grid, dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL(cats_gemm_skinny_bf16<3>, grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL(cats_gemm_skinny_bf16<4>, grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((cats_gemm_skinny_bf16<1, NW, GEMM_ST>), grid, dim3(64 * NW), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((cats_gemm_skinny_bf16<2, NW, GEMM_ST>), grid, dim3(64 * NW), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((cats_gemm_skinny_bf16<3, NW, GEMM_ST4>), grid, dim3(64 * NW), 0, st, a); break;
+        default: hipLaunchKernelGGL((cats_gemm_skinny_bf16<4, NW, GEMM_ST4>), grid, dim3(64 * NW), 0, st, a); break;
     }
 }

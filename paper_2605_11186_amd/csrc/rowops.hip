@@ -14,27 +14,38 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // x[t] <- (x_in[t] | embed[token[t]] | x[t]) + sum_s part[s][t];  xn[t] = rmsnorm(x[t]) * gain
-// One workgroup per row.
-constexpr int RN_THREADS = 256;
-constexpr int RN_MAX_PER_THREAD = 32;
+// One workgroup of 1024 threads per row; a thread owns float4 groups j = 4*tid + 4096*i, so
+// all of its partial-sum loads are independent 16-byte loads that can be in flight together.
+constexpr int RN_THREADS = 1024;
+constexpr int RN_MAX_GROUPS = 2;  // hidden <= 8192
 __global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNormArgs a) {
     __shared__ float red[RN_THREADS / 64];
     const int t = blockIdx.x;
     const int tid = threadIdx.x;
-    float v[RN_MAX_PER_THREAD];
+    f32x4 v[RN_MAX_GROUPS];
     float ss = 0.f;
     const size_t row = static_cast<size_t>(t) * a.H;
     const bf16_t* erow = a.embed ? a.embed + static_cast<size_t>(a.token[t]) * a.H : nullptr;
+    const bool write_x = erow || a.x_in || a.splits > 0;
 #pragma unroll
-    for (int i = 0; i < RN_MAX_PER_THREAD; ++i) {
-        const int j = tid + i * RN_THREADS;
+    for (int i = 0; i < RN_MAX_GROUPS; ++i) {
+        const int j = 4 * tid + 4 * RN_THREADS * i;
         if (j < a.H) {
-            float val = erow ? bf2f(erow[j]) : (a.x_in ? a.x_in[row + j] : a.x[row + j]);
-            for (int s = 0; s < a.splits; ++s)
-                val += a.part[(static_cast<size_t>(s) * a.T + t) * a.H + j];
+            f32x4 val;
+            if (erow) {
+                const uint2 e = *reinterpret_cast<const uint2*>(erow + j);
+                val = f32x4{__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xFFFF0000u),
+                            __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xFFFF0000u)};
+            } else {
+                val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
+            }
+            const float* pp = a.part + row + j;
+            const size_t stride = static_cast<size_t>(a.T) * a.H;
+#pragma unroll 8
+            for (int s = 0; s < a.splits; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
             v[i] = val;
-            ss += val * val;
-            if (erow || a.x_in || a.splits > 0) a.x[row + j] = val;
+            ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
+            if (write_x) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
         }
     }
     if (!a.gain) return;
@@ -46,9 +57,17 @@ __global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNorm
     for (int w = 0; w < RN_THREADS / 64; ++w) tot += red[w];
     const float scale = 1.0f / sqrtf(tot / static_cast<float>(a.H) + a.eps);
 #pragma unroll
-    for (int i = 0; i < RN_MAX_PER_THREAD; ++i) {
-        const int j = tid + i * RN_THREADS;
-        if (j < a.H) a.xn[row + j] = f2bf(v[i] * scale * bf2f(a.gain[j]));
+    for (int i = 0; i < RN_MAX_GROUPS; ++i) {
+        const int j = 4 * tid + 4 * RN_THREADS * i;
+        if (j < a.H) {
+            const uint2 gbits = *reinterpret_cast<const uint2*>(a.gain + j);
+            uint2 o;
+            o.x = pack_bf2(v[i][0] * scale * __uint_as_float(gbits.x << 16),
+                           v[i][1] * scale * __uint_as_float(gbits.x & 0xFFFF0000u));
+            o.y = pack_bf2(v[i][2] * scale * __uint_as_float(gbits.y << 16),
+                           v[i][3] * scale * __uint_as_float(gbits.y & 0xFFFF0000u));
+            *reinterpret_cast<uint2*>(a.xn + row + j) = o;
+        }
     }
 }
 
