@@ -53,30 +53,15 @@ inline int hip_fail(hipError_t e) {
 
 inline size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-// split-K factor: enough workgroups to give every CU a few, slices a multiple of
-// the kernel's K chunk.  CATS_GEMM_WGS overrides the target workgroup count.
+// Workgroups per GEMM launch: one per CU (the GEMM kernel's register footprint lets one
+// 512-thread workgroup live on a CU).  CATS_GEMM_WGS overrides it.
 int target_wgs() {
     static int v = [] {
         const char* e = std::getenv("CATS_GEMM_WGS");
         const int n = e ? std::atoi(e) : 0;
-        return n > 0 ? n : 512;
+        return n > 0 ? n : 256;
     }();
     return v;
-}
-
-struct SplitPlan {
-    int splits, k_per_split;
-};
-SplitPlan plan_split(int N, int K) {
-    const int tiles = (N + GEMM_BN - 1) / GEMM_BN;
-    int want = std::max(1, std::min(16, target_wgs() / tiles));
-    const int chunks = (K + GEMM_KC - 1) / GEMM_KC;
-    want = std::min(want, chunks);
-    const int cps = (chunks + want - 1) / want;  // chunks per split
-    SplitPlan p;
-    p.k_per_split = cps * GEMM_KC;
-    p.splits = (chunks + cps - 1) / cps;
-    return p;
 }
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
@@ -103,10 +88,10 @@ bool layer_ok(const cats_layer_weights* w) {
            w->g_ffn;
 }
 
-void enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, const void* w2,
-                  int seg_rows, int N, int K, int* splits_out, hipStream_t st) {
-    const SplitPlan p = plan_split(N, K);
+GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, const void* w2,
+                      int seg_rows, int N, int K, hipStream_t st) {
     GemmArgs g;
+    g.plan = make_gemm_plan(N, K, target_wgs());
     g.x = x;
     g.w[0] = static_cast<const bf16_t*>(w0);
     g.w[1] = static_cast<const bf16_t*>(w1 ? w1 : w0);
@@ -115,16 +100,15 @@ void enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, 
     g.N = N;
     g.K = K;
     g.T = c->T;
-    g.k_per_split = p.k_per_split;
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], st);
-    launch_gemm(g, p.splits, st);
+    launch_gemm(g, st);
     if (timed) {
         (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st);
         ++c->prof_n;
     }
-    *splits_out = p.splits;
+    return g.plan;
 }
 
 void enqueue_attention(cats_ctx* c, const bf16_t* q, const cats_kv_layer* kv, int ctx_len, bf16_t* out,
@@ -156,12 +140,11 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const cats_kv_layer* kv, in
 void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cats_kv_layer* kv,
                    int ctx_len, const void* next_gain, hipStream_t st) {
     const int H = c->d.hidden, F = c->d.ffn, T = c->T;
-    int splits = 1;
     // attention block
-    enqueue_gemm(c, c->xn, w->wq, w->wk, w->wv, H, 3 * H, H, &splits, st);
+    GemmPlan plan = enqueue_gemm(c, c->xn, w->wq, w->wk, w->wv, H, 3 * H, H, st);
     QkvRopeArgs qa;
     qa.part = c->part;
-    qa.splits = splits;
+    qa.plan = plan;
     qa.cs = c->rope_cs;
     qa.q = c->q;
     qa.kc = static_cast<bf16_t*>(kv->k);
@@ -174,14 +157,14 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.ctx_len = ctx_len;
     launch_qkv_rope(qa, st);
     enqueue_attention(c, c->q, kv, ctx_len, c->attn, st);
-    enqueue_gemm(c, c->attn, w->wo, nullptr, nullptr, H, H, H, &splits, st);
+    plan = enqueue_gemm(c, c->attn, w->wo, nullptr, nullptr, H, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
     rn.x_in = nullptr;
     rn.embed = nullptr;
     rn.token = nullptr;
     rn.part = c->part;
-    rn.splits = splits;
+    rn.plan = plan;
     rn.gain = static_cast<const bf16_t*>(w->g_ffn);
     rn.xn = c->xn;
     rn.T = T;
@@ -189,16 +172,16 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     rn.eps = c->d.rms_eps;
     launch_residual_norm(rn, st);
     // feed-forward block
-    enqueue_gemm(c, c->xn, w->w_gate, w->w_up, nullptr, F, 2 * F, H, &splits, st);
+    plan = enqueue_gemm(c, c->xn, w->w_gate, w->w_up, nullptr, F, 2 * F, H, st);
     SwigluArgs sa;
     sa.part = c->part;
-    sa.splits = splits;
+    sa.plan = plan;
     sa.h = c->hact;
     sa.T = T;
     sa.F = F;
     launch_swiglu(sa, st);
-    enqueue_gemm(c, c->hact, w->w_down, nullptr, nullptr, H, H, F, &splits, st);
-    rn.splits = splits;
+    plan = enqueue_gemm(c, c->hact, w->w_down, nullptr, nullptr, H, H, F, st);
+    rn.plan = plan;
     rn.gain = static_cast<const bf16_t*>(next_gain);
     launch_residual_norm(rn, st);
 }
@@ -216,11 +199,10 @@ void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
 
 void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
                      float* margin_out, hipStream_t st) {
-    int splits = 1;
-    enqueue_gemm(c, c->xn, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, &splits, st);
+    const GemmPlan plan = enqueue_gemm(c, c->xn, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, st);
     ArgmaxArgs am;
     am.part = c->part;
-    am.splits = splits;
+    am.plan = plan;
     am.T = c->T;
     am.V = c->d.vocab;
     am.logits = logits_out;
@@ -292,7 +274,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const int shapes[5][2] = {{3 * d.hidden, d.hidden}, {d.hidden, d.hidden}, {2 * d.ffn, d.hidden},
                               {d.hidden, d.ffn}, {d.vocab, d.hidden}};
     for (auto& s : shapes)
-        part_cols = std::max(part_cols, static_cast<size_t>(plan_split(s[0], s[1]).splits) * s[0]);
+        part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
+                                            make_gemm_plan(s[0], s[1], target_wgs()))) * s[0]);
     c->part_elems = part_cols * Tm;
     c->attn_max_chunks = 32;
     const size_t t_pad = (Tm + 31) / 32 * 32;
@@ -387,7 +370,7 @@ int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden,
     rn.embed = nullptr;
     rn.token = nullptr;
     rn.part = nullptr;
-    rn.splits = 0;
+    rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(w->g_attn);
     rn.xn = ctx->xn;
     rn.T = ctx->T;
@@ -435,7 +418,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final,
     rn.embed = nullptr;
     rn.token = nullptr;
     rn.part = nullptr;
-    rn.splits = 0;
+    rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(g_final);
     rn.xn = ctx->xn;
     rn.T = ctx->T;
@@ -471,7 +454,7 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     rn.embed = static_cast<const bf16_t*>(embed);
     rn.token = ctx->token;
     rn.part = nullptr;
-    rn.splits = 0;
+    rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : g_final);
     rn.xn = ctx->xn;
     rn.T = T;

@@ -27,16 +27,36 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ---------------------------------------------------------------- GEMM
-// Y[t][n] = sum_k X[t][k] * W[n][k] for t < T, written as float32 partial sums
-// part[split][t][n]; split s covers k in [s*k_per_split, min(K, (s+1)*k_per_split)).
+// Y[t][n] = sum_k X[t][k] * W[n][k] for t < T.  The work is the list of
+// (row tile, K chunk) items in tile-major order, cut into n_wgs equal contiguous
+// ranges, one per workgroup, so every CU streams the same number of weight bytes
+// whatever the shape.  A tile whose chunks are spread over several workgroups gets one
+// float32 partial result ("piece") from each of them: part[piece][t][n], piece =
+// workgroup - first workgroup of that tile.  Consumers add the pieces in index order.
+struct GemmPlan {
+    int bn;      // weight rows per tile
+    int chunks;  // K chunks per tile
+    int n_wgs;   // workgroups
+    int items;   // tiles * chunks
+};
+__host__ __device__ inline int plan_owner(const GemmPlan& p, int item) {
+    return static_cast<int>((static_cast<long long>(item + 1) * p.n_wgs - 1) / p.items);
+}
+__host__ __device__ inline int plan_item_begin(const GemmPlan& p, int wg) {
+    return static_cast<int>(static_cast<long long>(wg) * p.items / p.n_wgs);
+}
+__host__ __device__ inline int plan_first_wg(const GemmPlan& p, int tile) { return plan_owner(p, tile * p.chunks); }
+__host__ __device__ inline int plan_pieces(const GemmPlan& p, int tile) {
+    return plan_owner(p, tile * p.chunks + p.chunks - 1) - plan_owner(p, tile * p.chunks) + 1;
+}
 // W may be given as up to three row segments of seg_rows rows each (q|k|v, gate|up).
 struct GemmArgs {
     const bf16_t* x;  // [T][K]
     const bf16_t* w[3];
     int seg_rows;
     int N, K, T;
-    int k_per_split;  // multiple of the kernel's K chunk
-    float* part;
+    GemmPlan plan;
+    float* part;  // [pieces][T][N]
 };
 #ifndef CATS_GEMM_BN
 #define CATS_GEMM_BN 256
@@ -51,7 +71,17 @@ constexpr int GEMM_BN = CATS_GEMM_BN;    // weight rows per workgroup (32 per wa
 constexpr int GEMM_KC = 128;             // k elements per pipeline stage
 constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
 constexpr int GEMM_ST4 = CATS_GEMM_ST4;  // ... for T > 64 (larger accumulators)
-void launch_gemm(const GemmArgs& a, int splits, hipStream_t st);
+GemmPlan make_gemm_plan(int N, int K, int target_wgs);
+int gemm_plan_max_pieces(const GemmPlan& p);
+void launch_gemm(const GemmArgs& a, hipStream_t st);
+
+// Sum of the pieces of column n of row t (fixed order).
+__device__ __forceinline__ float sum_pieces(const float* part, const GemmPlan& p, int T, int N, int t, int n) {
+    const int pieces = plan_pieces(p, n / p.bn);
+    float v = 0.f;
+    for (int s = 0; s < pieces; ++s) v += part[(static_cast<size_t>(s) * T + t) * N + n];
+    return v;
+}
 
 // ---------------------------------------------------------------- row kernels
 struct ResidualNormArgs {
@@ -59,8 +89,8 @@ struct ResidualNormArgs {
     const float* x_in;      // optional [T][H]: start from this instead of x
     const bf16_t* embed;    // optional [V][H]: start from embed[token[t]]
     const int32_t* token;   // device [T]
-    const float* part;      // optional [splits][T][H] partial sums to add
-    int splits;
+    const float* part;      // optional [pieces][T][H] partial sums to add
+    GemmPlan plan;
     const bf16_t* gain;     // optional [H]: if given, xn = rmsnorm(x) * gain
     bf16_t* xn;             // [T][H]
     int T, H;
@@ -77,8 +107,8 @@ struct RopeTableArgs {
 void launch_rope_table(const RopeTableArgs& a, hipStream_t st);
 
 struct QkvRopeArgs {
-    const float* part;  // [splits][T][3H]: q | k | v
-    int splits;
+    const float* part;  // [pieces][T][3H]: q | k | v
+    GemmPlan plan;
     const float2* cs;   // [T][d/2]
     bf16_t* q;          // [T][H]
     bf16_t* kc;         // [nh][max_ctx][d]
@@ -88,16 +118,16 @@ struct QkvRopeArgs {
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
 
 struct SwigluArgs {
-    const float* part;  // [splits][T][2F]: gate | up
-    int splits;
+    const float* part;  // [pieces][T][2F]: gate | up
+    GemmPlan plan;
     bf16_t* h;          // [T][F]
     int T, F;
 };
 void launch_swiglu(const SwigluArgs& a, hipStream_t st);
 
 struct ArgmaxArgs {
-    const float* part;  // [splits][T][V]
-    int splits;
+    const float* part;  // [pieces][T][V]
+    GemmPlan plan;
     int T, V;
     float* logits;      // optional [T][V]
     int32_t* amax;      // [T]

@@ -8,9 +8,11 @@
 // staged in LDS and shared by all waves of the workgroup.  Each wave owns 32
 // weight rows.  The kernel is bound by HBM latency x bandwidth, so each wave keeps
 // a ring of ST-1 future K chunks (8 KB of weights each) in flight in registers.
-// The K range is cut into `splits` slices (grid.y) so that enough workgroups
-// exist to fill 256 CUs; the float32 partial sums go to part[split][t][n] and the
-// following epilogue kernel adds them up in a fixed order.
+// Work is balanced over the CUs: the (row tile, K chunk) items, in tile-major order,
+// are cut into one equal contiguous range per workgroup; a workgroup streams through
+// its range without a break (the ring keeps prefetching across tile boundaries) and
+// writes one float32 partial tile ("piece") for every tile it touches.  The following
+// epilogue kernel adds a tile's pieces in a fixed order.
 #include "common.hpp"
 
 namespace {
@@ -33,26 +35,20 @@ __device__ __forceinline__ void lds_barrier() {
 template <int TB, int NW, int ST>
 __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     constexpr int THREADS = 64 * NW;
+    constexpr int BN = 32 * NW;
     constexpr int XPT = TB * 512 / THREADS;       // u32x4 of the X tile per thread
     constexpr int XROWS_PER_PASS = THREADS / 16;  // tile rows covered by one pass of the block
     constexpr int NBUF = (ST % 2 == 0) ? 2 : ST;  // LDS buffers; the index is static under unrolling
+    static_assert(ST >= 2 && ST <= 3, "ring depth");
     __shared__ u32x4 xs[NBUF][TB * 32][XS_ROW];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
-
-    const int n = blockIdx.x * (32 * NW) + wave * 32 + col;
-    const bool n_ok = n < a.N;
-    const int nn = n_ok ? n : a.N - 1;
-    const int seg = nn / a.seg_rows;
-    const bf16_t* wseg = seg == 0 ? a.w[0] : (seg == 1 ? a.w[1] : a.w[2]);
-    const bf16_t* wrow = wseg + static_cast<size_t>(nn - seg * a.seg_rows) * a.K + 8 * g;
-
-    const int k_begin = blockIdx.y * a.k_per_split;
-    const int k_end = min(a.K, k_begin + a.k_per_split);
-    const int n_chunks = (k_end - k_begin + GEMM_KC - 1) / GEMM_KC;
-#define CATS_CHUNK_K(c) (k_begin + (c) * GEMM_KC)
+    const int wg = blockIdx.x;
+    const int C = a.plan.chunks;
+    const int item_lo = plan_item_begin(a.plan, wg);
+    const int n_items = plan_item_begin(a.plan, wg + 1) - item_lo;
 
     // staging assignment: thread -> (row, 16-byte column) of the X tile
     const int xr = tid >> 4, xc = tid & 15;
@@ -61,12 +57,11 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     u32x4 xst[ST][XPT];
     const u32x4 zero4 = u32x4{0u, 0u, 0u, 0u};
 
-    // The scheduling barriers keep the chunks' loads in issue order (the compiler would
-    // otherwise interleave them freely and then has to wait for the youngest one).
     // Loads are unconditional (clamped addresses) so that the pipeline is straight-line code:
     // a predicated load would put every load in its own basic block and the compiler would
     // then wait for ALL outstanding loads at each use.  Out-of-range X entries are zeroed by
-    // a select; the matching W values are finite and get multiplied by those zeros.
+    // a select at use; the matching W values are finite and get multiplied by those zeros.
+    // The scheduling barriers keep the chunks' loads in issue order.
     bool x_row_ok[XPT];
     const bf16_t* x_ptr[XPT];
 #pragma unroll
@@ -76,15 +71,26 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
         x_ptr[p] = a.x + static_cast<size_t>(min(r, a.T - 1)) * a.K;
     }
     const int k_last_x = a.K - 8, k_last_w = a.K - 16;
-#define CATS_LOAD_CHUNK(slot, k0)                                                                   \
+
+    // item (local index i) -> tile and first k of its chunk
+#define CATS_ITEM(i, tile_, k0_)                  \
+    const int gi_ = item_lo + (i);                \
+    const int tile_ = gi_ / C;                    \
+    const int k0_ = (gi_ - tile_ * C) * GEMM_KC;
+
+#define CATS_LOAD_CHUNK(slot, i)                                                                    \
     {                                                                                               \
-        const int k0_ = (k0);                                                                       \
-        const int kx = k0_ + 8 * xc;                                                                \
+        CATS_ITEM(i, lt_, lk_)                                                                      \
+        const int ln_ = min(lt_ * BN + wave * 32 + col, a.N - 1);                                   \
+        const int lseg_ = ln_ / a.seg_rows;                                                         \
+        const bf16_t* lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                \
+                            static_cast<size_t>(ln_ - lseg_ * a.seg_rows) * a.K + 8 * g;            \
+        const int kx = lk_ + 8 * xc;                                                                \
         _Pragma("unroll") for (int p = 0; p < XPT; ++p)                                             \
             xst[slot][p] = *reinterpret_cast<const u32x4*>(x_ptr[p] + min(kx, k_last_x));           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
-            wst[slot][j] = *reinterpret_cast<const u32x4*>(wrow + min(k0_ + 16 * j, k_last_w));     \
+            wst[slot][j] = *reinterpret_cast<const u32x4*>(lw_ + min(lk_ + 16 * j, k_last_w));      \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
@@ -94,20 +100,18 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
 
-    // prologue: chunks 0 .. ST-2 in flight
-#pragma unroll
-    for (int s = 0; s < ST - 1; ++s) CATS_LOAD_CHUNK(s, CATS_CHUNK_K(s))
-
-    // One pipeline step: stage X of chunk c (ring slot s) in LDS, optionally refill the slot
-    // freed by the previous step with chunk c+ST-1, multiply.
-#define CATS_STEP(s, c, REFILL)                                                                     \
+    // One pipeline step: stage X of item i (ring slot s) in LDS, optionally refill the slot
+    // freed by the previous step with item i+ST-1, multiply, and hand the partial tile over
+    // when the tile (or this workgroup's range) ends.
+#define CATS_STEP(s, i, REFILL)                                                                     \
     {                                                                                               \
         constexpr int buf = (s) % NBUF;                                                             \
+        CATS_ITEM(i, tile, k0)                                                                      \
         _Pragma("unroll") for (int p = 0; p < XPT; ++p) /* zero what lies outside the tile */       \
             xs[buf][xr + XROWS_PER_PASS * p][xc] =                                                  \
-                (x_row_ok[p] && CATS_CHUNK_K(c) + 8 * xc < k_end) ? xst[s][p] : zero4;      \
+                (x_row_ok[p] && k0 + 8 * xc < a.K) ? xst[s][p] : zero4;                             \
         lds_barrier();                                                                              \
-        if (REFILL) CATS_LOAD_CHUNK(((s) + ST - 1) % ST, CATS_CHUNK_K((c) + ST - 1))        \
+        if (REFILL) CATS_LOAD_CHUNK(((s) + ST - 1) % ST, min((i) + ST - 1, n_items - 1))            \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
             const bf16x8 b = as_bf16x8(wst[s][j]);                                                  \
             _Pragma("unroll") for (int tb = 0; tb < TB; ++tb) {                                     \
@@ -115,52 +119,88 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc[tb], 0, 0, 0);         \
             }                                                                                       \
         }                                                                                           \
+        if (k0 + GEMM_KC >= a.K || (i) == n_items - 1) {                                            \
+            const int n = tile * BN + wave * 32 + col;                                              \
+            if (n < a.N) {                                                                          \
+                const int piece = wg - plan_first_wg(a.plan, tile);                                 \
+                float* out = a.part + static_cast<size_t>(piece) * a.T * a.N + n;                   \
+                _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                   \
+                    _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                \
+                    const int t = tb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);                         \
+                    if (t < a.T) out[static_cast<size_t>(t) * a.N] = acc[tb][r];                    \
+                }                                                                                   \
+            }                                                                                       \
+            _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                       \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;                    \
+        }                                                                                           \
     }
 
-    // Full groups of ST chunks run without any inner condition: a conditional step inside
-    // the loop would give the compiler a (never taken) path on which ring loads stay
-    // unconsumed, and it would then drain all loads at the loop head.
-    static_assert(ST >= 2 && ST <= 4, "ring depth");
+    // prologue: items 0 .. ST-2 in flight (indices past the range are clamped: harmless reloads)
+#pragma unroll
+    for (int s = 0; s < ST - 1; ++s) CATS_LOAD_CHUNK(s, min(s, n_items - 1))
+
+    // Full groups of ST items whose refills all lie inside the range run without any
+    // condition: a conditional step inside the loop would give the compiler a (never taken)
+    // path on which ring loads stay unconsumed, and it would drain all loads at the loop head.
     int c0 = 0;
-    for (; c0 + ST <= n_chunks; c0 += ST) {
+    for (; c0 + 2 * ST - 1 <= n_items; c0 += ST) {
         CATS_STEP(0, c0, true)
         CATS_STEP(1, c0 + 1, true)
         if constexpr (ST > 2) CATS_STEP(2, c0 + 2, true)
-        if constexpr (ST > 3) CATS_STEP(3, c0 + 3, true)
     }
-    // tail: fewer than ST chunks left, already in flight
-    if (c0 < n_chunks) {
-        CATS_STEP(0, c0, false)
-        if (c0 + 1 < n_chunks) {
-            CATS_STEP(1, c0 + 1, false)
-            if constexpr (ST > 3) {
-                if (c0 + 2 < n_chunks) CATS_STEP(2, c0 + 2, false)
-            } else if constexpr (ST > 2) {
-                if (c0 + 2 < n_chunks) CATS_STEP(2, c0 + 2, false)
+    // tail: at most 2*ST-2 items left; item c0+j sits in ring slot j % ST and is refilled
+    // from only while the refill index stays inside the range
+#define CATS_TAIL(j)                                                 \
+    if (c0 + (j) + ST - 1 < n_items) {                               \
+        CATS_STEP((j) % ST, c0 + (j), true)                          \
+    } else {                                                         \
+        CATS_STEP((j) % ST, c0 + (j), false)                         \
+    }
+    if (c0 < n_items) {
+        CATS_TAIL(0)
+        if (c0 + 1 < n_items) {
+            CATS_TAIL(1)
+            if constexpr (ST > 2) {
+                if (c0 + 2 < n_items) {
+                    CATS_TAIL(2)
+                    if (c0 + 3 < n_items) {
+                        CATS_TAIL(3)
+                    }
+                }
             }
         }
     }
+#undef CATS_TAIL
 #undef CATS_STEP
-#undef CATS_CHUNK_K
 #undef CATS_LOAD_CHUNK
-
-    if (n_ok) {
-        float* out = a.part + static_cast<size_t>(blockIdx.y) * a.T * a.N + n;
-#pragma unroll
-        for (int tb = 0; tb < TB; ++tb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int t = tb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (t < a.T) out[static_cast<size_t>(t) * a.N] = acc[tb][r];
-            }
-    }
+#undef CATS_ITEM
 }
 
 }  // namespace
 
-void launch_gemm(const GemmArgs& a, int splits, hipStream_t st) {
+GemmPlan make_gemm_plan(int N, int K, int target_wgs) {
+    GemmPlan p;
+    p.bn = GEMM_BN;
+    p.chunks = (K + GEMM_KC - 1) / GEMM_KC;
+    const int tiles = (N + GEMM_BN - 1) / GEMM_BN;
+    p.items = tiles * p.chunks;
+    p.n_wgs = target_wgs < p.items ? target_wgs : p.items;
+    return p;
+}
+
+int gemm_plan_max_pieces(const GemmPlan& p) {
+    const int tiles = p.items / p.chunks;
+    int m = 1;
+    for (int t = 0; t < tiles; ++t) {
+        const int k = plan_pieces(p, t);
+        m = k > m ? k : m;
+    }
+    return m;
+}
+
+void launch_gemm(const GemmArgs& a, hipStream_t st) {
     constexpr int NW = GEMM_BN / 32;
-    dim3 grid((a.N + GEMM_BN - 1) / GEMM_BN, splits);
+    dim3 grid(a.plan.n_wgs);
     const int tb = (a.T + 31) / 32;
     switch (tb) {
         case 1: hipLaunchKernelGGL((cats_gemm_skinny_bf16<1, NW, GEMM_ST>), grid, dim3(64 * NW), 0, st, a); break;

@@ -26,7 +26,7 @@ __global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNorm
     float ss = 0.f;
     const size_t row = static_cast<size_t>(t) * a.H;
     const bf16_t* erow = a.embed ? a.embed + static_cast<size_t>(a.token[t]) * a.H : nullptr;
-    const bool write_x = erow || a.x_in || a.splits > 0;
+    const bool write_x = erow || a.x_in || a.part;
 #pragma unroll
     for (int i = 0; i < RN_MAX_GROUPS; ++i) {
         const int j = 4 * tid + 4 * RN_THREADS * i;
@@ -39,10 +39,13 @@ __global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNorm
             } else {
                 val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
             }
-            const float* pp = a.part + row + j;
-            const size_t stride = static_cast<size_t>(a.T) * a.H;
+            if (a.part) {
+                const float* pp = a.part + row + j;
+                const size_t stride = static_cast<size_t>(a.T) * a.H;
+                const int pieces = plan_pieces(a.plan, j / a.plan.bn);
 #pragma unroll 8
-            for (int s = 0; s < a.splits; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
+                for (int s = 0; s < pieces; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
+            }
             v[i] = val;
             ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
             if (write_x) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
@@ -90,16 +93,14 @@ __global__ void cats_qkv_rope_append(QkvRopeArgs a) {
     const int t = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
     const int half = a.d / 2;
     const int N = 3 * a.H;
-    float v6[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < a.splits; ++s) {
-        const float* p = a.part + (static_cast<size_t>(s) * a.T + t) * N + h * a.d + j;
-        v6[0] += p[0];
-        v6[1] += p[half];
-        v6[2] += p[a.H];
-        v6[3] += p[a.H + half];
-        v6[4] += p[2 * a.H];
-        v6[5] += p[2 * a.H + half];
-    }
+    float v6[6];
+    const int c0 = h * a.d + j;
+    v6[0] = sum_pieces(a.part, a.plan, a.T, N, t, c0);
+    v6[1] = sum_pieces(a.part, a.plan, a.T, N, t, c0 + half);
+    v6[2] = sum_pieces(a.part, a.plan, a.T, N, t, a.H + c0);
+    v6[3] = sum_pieces(a.part, a.plan, a.T, N, t, a.H + c0 + half);
+    v6[4] = sum_pieces(a.part, a.plan, a.T, N, t, 2 * a.H + c0);
+    v6[5] = sum_pieces(a.part, a.plan, a.T, N, t, 2 * a.H + c0 + half);
     const float2 cs = a.cs[t * half + j];
     const float q0 = v6[0] * cs.x - v6[1] * cs.y, q1 = v6[0] * cs.y + v6[1] * cs.x;
     const float k0 = v6[2] * cs.x - v6[3] * cs.y, k1 = v6[2] * cs.y + v6[3] * cs.x;
@@ -120,12 +121,8 @@ __global__ void cats_swiglu(SwigluArgs a) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= a.T * a.F) return;
     const int t = idx / a.F, n = idx - t * a.F;
-    float gt = 0.f, up = 0.f;
-    for (int s = 0; s < a.splits; ++s) {
-        const float* p = a.part + (static_cast<size_t>(s) * a.T + t) * (2 * a.F) + n;
-        gt += p[0];
-        up += p[a.F];
-    }
+    const float gt = sum_pieces(a.part, a.plan, a.T, 2 * a.F, t, n);
+    const float up = sum_pieces(a.part, a.plan, a.T, 2 * a.F, t, a.F + n);
     a.h[idx] = f2bf(gt / (1.0f + __expf(-gt)) * up);
 }
 
@@ -139,8 +136,7 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
     float best = -INFINITY, second = -INFINITY;
     int bidx = 0x7fffffff;
     for (int v = tid; v < a.V; v += AM_THREADS) {
-        float val = 0.f;
-        for (int s = 0; s < a.splits; ++s) val += a.part[(static_cast<size_t>(s) * a.T + t) * a.V + v];
+        const float val = sum_pieces(a.part, a.plan, a.T, a.V, t, v);
         if (a.logits) a.logits[static_cast<size_t>(t) * a.V + v] = val;
         if (val > best) {  // indices ascend within a thread: strict > keeps the lowest
             second = best;
