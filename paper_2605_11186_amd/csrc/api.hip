@@ -19,10 +19,11 @@ struct cats_ctx {
     int T;  // 0 = no tree set
     // scratch
     float* x;        // [max_tree][H] residual stream
-    bf16_t* xn;      // [max_tree][H] normalised activations (GEMM input)
-    bf16_t* q;       // [max_tree][H]
-    bf16_t* attn;    // [max_tree][H]
-    bf16_t* hact;    // [max_tree][F]
+    // activations that feed a GEMM or the attention products: high and low bf16 parts
+    bf16_t *xn, *xn_lo;      // [max_tree][H] normalised rows
+    bf16_t *q, *q_lo;        // [max_tree][H] rotated queries
+    bf16_t *attn, *attn_lo;  // [max_tree][H] attention output
+    bf16_t *hact, *hact_lo;  // [max_tree][F] SwiGLU output
     float* part;     // split-K partial sums
     size_t part_elems;
     float2* rope_cs;  // [max_tree][d/2]
@@ -88,11 +89,12 @@ bool layer_ok(const cats_layer_weights* w) {
            w->g_ffn;
 }
 
-GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* w1, const void* w2,
+GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const void* w0, const void* w1, const void* w2,
                       int seg_rows, int N, int K, hipStream_t st) {
     GemmArgs g;
     g.plan = make_gemm_plan(N, K, target_wgs());
     g.x = x;
+    g.x_lo = x_lo;
     g.w[0] = static_cast<const bf16_t*>(w0);
     g.w[1] = static_cast<const bf16_t*>(w1 ? w1 : w0);
     g.w[2] = static_cast<const bf16_t*>(w2 ? w2 : w0);
@@ -111,10 +113,12 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const void* w0, const void* 
     return g.plan;
 }
 
-void enqueue_attention(cats_ctx* c, const bf16_t* q, const cats_kv_layer* kv, int ctx_len, bf16_t* out,
-                       hipStream_t st) {
+void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const cats_kv_layer* kv,
+                       int ctx_len, bf16_t* out, bf16_t* out_lo, hipStream_t st) {
     AttnArgs a;
     a.q = q;
+    a.q_lo = q_lo;
+    a.out_lo = out_lo;
     a.kc = static_cast<const bf16_t*>(kv->k);
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.parent = c->parent;
@@ -141,12 +145,13 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
                    int ctx_len, const void* next_gain, hipStream_t st) {
     const int H = c->d.hidden, F = c->d.ffn, T = c->T;
     // attention block
-    GemmPlan plan = enqueue_gemm(c, c->xn, w->wq, w->wk, w->wv, H, 3 * H, H, st);
+    GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, H, 3 * H, H, st);
     QkvRopeArgs qa;
     qa.part = c->part;
     qa.plan = plan;
     qa.cs = c->rope_cs;
     qa.q = c->q;
+    qa.q_lo = c->q_lo;
     qa.kc = static_cast<bf16_t*>(kv->k);
     qa.vt = static_cast<bf16_t*>(kv->v);
     qa.T = T;
@@ -156,8 +161,8 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.max_ctx = c->d.max_ctx;
     qa.ctx_len = ctx_len;
     launch_qkv_rope(qa, st);
-    enqueue_attention(c, c->q, kv, ctx_len, c->attn, st);
-    plan = enqueue_gemm(c, c->attn, w->wo, nullptr, nullptr, H, H, H, st);
+    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, st);
+    plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, H, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
     rn.x_in = nullptr;
@@ -167,20 +172,22 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     rn.plan = plan;
     rn.gain = static_cast<const bf16_t*>(w->g_ffn);
     rn.xn = c->xn;
+    rn.xn_lo = c->xn_lo;
     rn.T = T;
     rn.H = H;
     rn.eps = c->d.rms_eps;
     launch_residual_norm(rn, st);
     // feed-forward block
-    plan = enqueue_gemm(c, c->xn, w->w_gate, w->w_up, nullptr, F, 2 * F, H, st);
+    plan = enqueue_gemm(c, c->xn, c->xn_lo, w->w_gate, w->w_up, nullptr, F, 2 * F, H, st);
     SwigluArgs sa;
     sa.part = c->part;
     sa.plan = plan;
     sa.h = c->hact;
+    sa.h_lo = c->hact_lo;
     sa.T = T;
     sa.F = F;
     launch_swiglu(sa, st);
-    plan = enqueue_gemm(c, c->hact, w->w_down, nullptr, nullptr, H, H, F, st);
+    plan = enqueue_gemm(c, c->hact, c->hact_lo, w->w_down, nullptr, nullptr, H, H, F, st);
     rn.plan = plan;
     rn.gain = static_cast<const bf16_t*>(next_gain);
     launch_residual_norm(rn, st);
@@ -199,7 +206,7 @@ void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
 
 void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
                      float* margin_out, hipStream_t st) {
-    const GemmPlan plan = enqueue_gemm(c, c->xn, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, st);
+    const GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, st);
     ArgmaxArgs am;
     am.part = c->part;
     am.plan = plan;
@@ -288,6 +295,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_tok = take(Tm * 4), o_par = take(Tm * 4), o_dep = take(Tm * 4);
     const size_t o_x = take(Tm * H * 4), o_xn = take(Tm * H * 2), o_q = take(Tm * H * 2);
     const size_t o_attn = take(Tm * H * 2), o_h = take(Tm * F * 2);
+    const size_t o_xn_lo = take(Tm * H * 2), o_q_lo = take(Tm * H * 2), o_attn_lo = take(Tm * H * 2);
+    const size_t o_h_lo = take(Tm * F * 2);
     const size_t o_part = take(c->part_elems * 4);
     const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
@@ -313,6 +322,10 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->q = reinterpret_cast<bf16_t*>(b + o_q);
     c->attn = reinterpret_cast<bf16_t*>(b + o_attn);
     c->hact = reinterpret_cast<bf16_t*>(b + o_h);
+    c->xn_lo = reinterpret_cast<bf16_t*>(b + o_xn_lo);
+    c->q_lo = reinterpret_cast<bf16_t*>(b + o_q_lo);
+    c->attn_lo = reinterpret_cast<bf16_t*>(b + o_attn_lo);
+    c->hact_lo = reinterpret_cast<bf16_t*>(b + o_h_lo);
     c->part = reinterpret_cast<float*>(b + o_part);
     c->rope_cs = reinterpret_cast<float2*>(b + o_cs);
     c->attn_po = reinterpret_cast<float*>(b + o_po);
@@ -373,6 +386,7 @@ int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden,
     rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(w->g_attn);
     rn.xn = ctx->xn;
+    rn.xn_lo = ctx->xn_lo;
     rn.T = ctx->T;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
@@ -387,8 +401,8 @@ int cats_tree_attention(cats_ctx* ctx, const void* q, const cats_kv_layer* kv, i
     const int rc = check_ctx_len(ctx, ctx_len);
     if (rc != CATS_OK) return rc;
     if (!q || !out || !kv_ok(kv, 0, 1)) return CATS_EINVAL;
-    enqueue_attention(ctx, static_cast<const bf16_t*>(q), kv, ctx_len, static_cast<bf16_t*>(out),
-                      as_stream(stream));
+    enqueue_attention(ctx, static_cast<const bf16_t*>(q), nullptr, kv, ctx_len, static_cast<bf16_t*>(out),
+                      nullptr, as_stream(stream));
     HIP_TRY(hipGetLastError());
     return CATS_OK;
 }
@@ -421,6 +435,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final,
     rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(g_final);
     rn.xn = ctx->xn;
+    rn.xn_lo = ctx->xn_lo;
     rn.T = ctx->T;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
@@ -457,6 +472,7 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     rn.plan = GemmPlan{1, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : g_final);
     rn.xn = ctx->xn;
+    rn.xn_lo = ctx->xn_lo;
     rn.T = T;
     rn.H = H;
     rn.eps = ctx->d.rms_eps;

@@ -10,7 +10,8 @@
 // lane owns ONE query column and 8 keys of every 32-key block: the running
 // max / sum of the online softmax are per-lane scalars shared by four lanes and
 // reduced with two wave shuffles, and the probabilities are already laid out as
-// the B operand of the second product O^T = V^T P^T.  V is cached transposed
+// the B operand of the second product O^T = V^T P^T.  Queries and probabilities are
+// fed as high + low bf16 parts so that only the cache's own bf16 format limits accuracy.  V is cached transposed
 // ([head][dim][row]) so that its A operand is a plain 128-bit load as well; no
 // LDS round trip for K, V or P.  Chunks are merged afterwards with the usual
 // log-sum-exp rescaling.
@@ -51,17 +52,22 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
         }
     }
 
-    // Q^T fragments (B operand of the score product): column = query, k = dim
-    bf16x8 qf[2][KS];
+    // Q^T fragments (B operand of the score product): column = query, k = dim; queries come
+    // as high + low bf16 parts (the low part may be absent)
+    bf16x8 qf[2][KS], qfl[2][KS];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const int t = qbase + 16 * qb + m;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            u32x4 v = u32x4{0u, 0u, 0u, 0u};
-            if (t < T)
-                v = *reinterpret_cast<const u32x4*>(a.q + static_cast<size_t>(t) * a.H + h * D + 32 * s + 8 * q4);
+            u32x4 v = u32x4{0u, 0u, 0u, 0u}, vl = u32x4{0u, 0u, 0u, 0u};
+            const size_t off = static_cast<size_t>(min(t, T - 1)) * a.H + h * D + 32 * s + 8 * q4;
+            if (t < T) {
+                v = *reinterpret_cast<const u32x4*>(a.q + off);
+                if (a.q_lo) vl = *reinterpret_cast<const u32x4*>(a.q_lo + off);
+            }
             qf[qb][s] = as_bf16x8(v);
+            qfl[qb][s] = as_bf16x8(vl);
         }
     }
 
@@ -119,8 +125,10 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
             for (int b = 0; b < 2; ++b) {
                 st[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int s = 0; s < KS; ++s)
+                for (int s = 0; s < KS; ++s) {
                     st[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][s], qf[qb][s], st[b], 0, 0, 0);
+                    st[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[b][s], qfl[qb][s], st[b], 0, 0, 0);
+                }
             }
             // this lane: query column m of group qb, keys key0 + 4*b + r
             float sc[8];
@@ -158,13 +166,21 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
                 psum += p[i];
             }
             lrun[qb] = lrun[qb] * alpha + psum;
-            const u32x4 pv = {pack_bf2(p[0], p[1]), pack_bf2(p[2], p[3]), pack_bf2(p[4], p[5]),
-                              pack_bf2(p[6], p[7])};
-            const bf16x8 pf = as_bf16x8(pv);
+            // probabilities as high + low bf16 parts: the second product sees them to ~16 bits
+            u32x4 pv, pvl;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t hi, lo;
+                split_bf2(p[2 * e], p[2 * e + 1], hi, lo);
+                pv[e] = hi;
+                pvl[e] = lo;
+            }
+            const bf16x8 pf = as_bf16x8(pv), pfl = as_bf16x8(pvl);
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
                 o[qb][db] *= alpha;
                 o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[qb][db], 0, 0, 0);
+                o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pfl, o[qb][db], 0, 0, 0);
             }
         }
     }
@@ -204,7 +220,11 @@ __global__ void cats_tree_attention_merge(AttnArgs a) {
         num += wgt * a.po[slot * D + dd];
         den += wgt * a.pml[slot * 2 + 1];
     }
-    a.out[static_cast<size_t>(t) * a.H + h * D + dd] = f2bf(num / den);
+    const float r = num / den;
+    const bf16_t hi = f2bf(r);
+    const size_t o = static_cast<size_t>(t) * a.H + h * D + dd;
+    a.out[o] = hi;
+    if (a.out_lo) a.out_lo[o] = f2bf(r - bf2f(hi));
 }
 
 }  // namespace

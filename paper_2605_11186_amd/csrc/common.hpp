@@ -24,6 +24,13 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
     return static_cast<uint32_t>(f2bf(lo)) | (static_cast<uint32_t>(f2bf(hi)) << 16);
 }
 
+// x ~= hi + lo with hi = bf16(x), lo = bf16(x - hi)
+__device__ __forceinline__ void split_bf2(float a, float b, uint32_t& hi, uint32_t& lo) {
+    const bf16_t ah = f2bf(a), bh = f2bf(b);
+    hi = static_cast<uint32_t>(ah) | (static_cast<uint32_t>(bh) << 16);
+    lo = pack_bf2(a - bf2f(ah), b - bf2f(bh));
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ---------------------------------------------------------------- GEMM
@@ -50,8 +57,13 @@ __host__ __device__ inline int plan_pieces(const GemmPlan& p, int tile) {
     return plan_owner(p, tile * p.chunks + p.chunks - 1) - plan_owner(p, tile * p.chunks) + 1;
 }
 // W may be given as up to three row segments of seg_rows rows each (q|k|v, gate|up).
+// Activations are carried as a pair of bf16 arrays (hi, lo) with x = hi + lo to about 16
+// mantissa bits: bf16 weights times (hi + lo) on the bf16 MFMA keeps the products close to
+// fp32 accuracy, which the exact-acceptance requirement needs (a single bf16 rounding of
+// every GEMM input moves 7B-scale logits by several 1e-2).
 struct GemmArgs {
-    const bf16_t* x;  // [T][K]
+    const bf16_t* x;     // [T][K] high parts
+    const bf16_t* x_lo;  // [T][K] low parts
     const bf16_t* w[3];
     int seg_rows;
     int N, K, T;
@@ -62,7 +74,7 @@ struct GemmArgs {
 #define CATS_GEMM_BN 256
 #endif
 #ifndef CATS_GEMM_ST
-#define CATS_GEMM_ST 3
+#define CATS_GEMM_ST 2
 #endif
 #ifndef CATS_GEMM_ST4
 #define CATS_GEMM_ST4 2
@@ -92,7 +104,8 @@ struct ResidualNormArgs {
     const float* part;      // optional [pieces][T][H] partial sums to add
     GemmPlan plan;
     const bf16_t* gain;     // optional [H]: if given, xn = rmsnorm(x) * gain
-    bf16_t* xn;             // [T][H]
+    bf16_t* xn;             // [T][H] high parts of the normalised row
+    bf16_t* xn_lo;          // [T][H] low parts
     int T, H;
     float eps;
 };
@@ -110,7 +123,8 @@ struct QkvRopeArgs {
     const float* part;  // [pieces][T][3H]: q | k | v
     GemmPlan plan;
     const float2* cs;   // [T][d/2]
-    bf16_t* q;          // [T][H]
+    bf16_t* q;          // [T][H] high parts of the rotated queries
+    bf16_t* q_lo;       // [T][H] low parts
     bf16_t* kc;         // [nh][max_ctx][d]
     bf16_t* vt;         // [nh][d][max_ctx]
     int T, H, nh, d, max_ctx, ctx_len;
@@ -120,7 +134,8 @@ void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
 struct SwigluArgs {
     const float* part;  // [pieces][T][2F]: gate | up
     GemmPlan plan;
-    bf16_t* h;          // [T][F]
+    bf16_t* h;          // [T][F] high parts
+    bf16_t* h_lo;       // [T][F] low parts
     int T, F;
 };
 void launch_swiglu(const SwigluArgs& a, hipStream_t st);
@@ -138,6 +153,7 @@ void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
 // ---------------------------------------------------------------- attention
 struct AttnArgs {
     const bf16_t* q;        // [T][H]
+    const bf16_t* q_lo;     // optional [T][H] low parts of q
     const bf16_t* kc;       // [nh][max_ctx][d]
     const bf16_t* vt;       // [nh][d][max_ctx]
     const int32_t* parent;  // device [T]
@@ -146,6 +162,7 @@ struct AttnArgs {
     float* po;              // [nh][n_chunks][t_pad][d]
     float* pml;             // [nh][n_chunks][t_pad][2]
     bf16_t* out;            // [T][H]
+    bf16_t* out_lo;         // optional [T][H] low parts of the output
 };
 constexpr int ATTN_KB = 32;  // keys per block
 void launch_attention(const AttnArgs& a, hipStream_t st);

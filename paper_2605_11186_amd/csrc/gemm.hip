@@ -4,8 +4,8 @@
 //
 // Y[t][n] = sum_k X[t][k] W[n][k], T <= 128 rows, N and K large.  Every weight
 // element is loaded from HBM exactly once, straight into the MFMA B-operand
-// registers by 128-bit loads; the T activations of the current K chunk are
-// staged in LDS and shared by all waves of the workgroup.  Each wave owns 32
+// registers by 128-bit loads; the T activations of the current K chunk (a high and a
+// low bf16 part each, see GemmArgs) are staged in LDS and shared by all waves.  Each wave owns 32
 // weight rows.  The kernel is bound by HBM latency x bandwidth, so each wave keeps
 // a ring of ST-1 future K chunks (8 KB of weights each) in flight in registers.
 // Work is balanced over the CUs: the (row tile, K chunk) items, in tile-major order,
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     constexpr int XROWS_PER_PASS = THREADS / 16;  // tile rows covered by one pass of the block
     constexpr int NBUF = (ST % 2 == 0) ? 2 : ST;  // LDS buffers; the index is static under unrolling
     static_assert(ST >= 2 && ST <= 3, "ring depth");
-    __shared__ u32x4 xs[NBUF][TB * 32][XS_ROW];
+    __shared__ u32x4 xs[NBUF][2][TB * 32][XS_ROW];  // [.][0] high parts, [.][1] low parts
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     const int xr = tid >> 4, xc = tid & 15;
 
     u32x4 wst[ST][8];
-    u32x4 xst[ST][XPT];
+    u32x4 xst[2 * XPT];  // X of the next item only: it comes from L2, one step ahead is enough
     const u32x4 zero4 = u32x4{0u, 0u, 0u, 0u};
 
     // Loads are unconditional (clamped addresses) so that the pipeline is straight-line code:
@@ -63,12 +63,12 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     // a select at use; the matching W values are finite and get multiplied by those zeros.
     // The scheduling barriers keep the chunks' loads in issue order.
     bool x_row_ok[XPT];
-    const bf16_t* x_ptr[XPT];
+    size_t x_off[XPT];
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
         const int r = xr + XROWS_PER_PASS * p;
         x_row_ok[p] = r < a.T;
-        x_ptr[p] = a.x + static_cast<size_t>(min(r, a.T - 1)) * a.K;
+        x_off[p] = static_cast<size_t>(min(r, a.T - 1)) * a.K;
     }
     const int k_last_x = a.K - 8, k_last_w = a.K - 16;
 
@@ -78,17 +78,25 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     const int tile_ = gi_ / C;                    \
     const int k0_ = (gi_ - tile_ * C) * GEMM_KC;
 
-#define CATS_LOAD_CHUNK(slot, i)                                                                    \
+#define CATS_LOAD_X(i)                                                                              \
+    {                                                                                               \
+        CATS_ITEM(i, xt_, xk_)                                                                      \
+        (void)xt_;                                                                                  \
+        const int kx = xk_ + 8 * xc;                                                                \
+        _Pragma("unroll") for (int p = 0; p < XPT; ++p) {                                           \
+            const size_t xo_ = x_off[p] + min(kx, k_last_x);                                        \
+            xst[2 * p] = *reinterpret_cast<const u32x4*>(a.x + xo_);                                \
+            xst[2 * p + 1] = *reinterpret_cast<const u32x4*>(a.x_lo + xo_);                         \
+        }                                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+    }
+#define CATS_LOAD_W(slot, i)                                                                        \
     {                                                                                               \
         CATS_ITEM(i, lt_, lk_)                                                                      \
         const int ln_ = min(lt_ * BN + wave * 32 + col, a.N - 1);                                   \
         const int lseg_ = ln_ / a.seg_rows;                                                         \
         const bf16_t* lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                \
                             static_cast<size_t>(ln_ - lseg_ * a.seg_rows) * a.K + 8 * g;            \
-        const int kx = lk_ + 8 * xc;                                                                \
-        _Pragma("unroll") for (int p = 0; p < XPT; ++p)                                             \
-            xst[slot][p] = *reinterpret_cast<const u32x4*>(x_ptr[p] + min(kx, k_last_x));           \
-        __builtin_amdgcn_sched_barrier(0);                                                          \
         _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
             wst[slot][j] = *reinterpret_cast<const u32x4*>(lw_ + min(lk_ + 16 * j, k_last_w));      \
         __builtin_amdgcn_sched_barrier(0);                                                          \
@@ -100,24 +108,31 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
 
-    // One pipeline step: stage X of item i (ring slot s) in LDS, optionally refill the slot
-    // freed by the previous step with item i+ST-1, multiply, and hand the partial tile over
+    // One pipeline step: stage X of item i in LDS, fetch X of item i+1, optionally refill the
+    // W ring slot freed by the previous step with item i+ST-1, multiply W (ring slot s), and hand the partial tile over
     // when the tile (or this workgroup's range) ends.
 #define CATS_STEP(s, i, REFILL)                                                                     \
     {                                                                                               \
         constexpr int buf = (s) % NBUF;                                                             \
         CATS_ITEM(i, tile, k0)                                                                      \
-        _Pragma("unroll") for (int p = 0; p < XPT; ++p) /* zero what lies outside the tile */       \
-            xs[buf][xr + XROWS_PER_PASS * p][xc] =                                                  \
-                (x_row_ok[p] && k0 + 8 * xc < a.K) ? xst[s][p] : zero4;                             \
+        _Pragma("unroll") for (int p = 0; p < XPT; ++p) { /* zero what lies outside the tile */     \
+            const bool ok_ = x_row_ok[p] && k0 + 8 * xc < a.K;                                      \
+            xs[buf][0][xr + XROWS_PER_PASS * p][xc] = ok_ ? xst[2 * p] : zero4;                     \
+            xs[buf][1][xr + XROWS_PER_PASS * p][xc] = ok_ ? xst[2 * p + 1] : zero4;                 \
+        }                                                                                           \
         lds_barrier();                                                                              \
-        if (REFILL) CATS_LOAD_CHUNK(((s) + ST - 1) % ST, min((i) + ST - 1, n_items - 1))            \
+        CATS_LOAD_X(min((i) + 1, n_items - 1))                                                      \
+        if (REFILL) CATS_LOAD_W(((s) + ST - 1) % ST, min((i) + ST - 1, n_items - 1))                \
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
             const bf16x8 b = as_bf16x8(wst[s][j]);                                                  \
             _Pragma("unroll") for (int tb = 0; tb < TB; ++tb) {                                     \
-                const bf16x8 av = as_bf16x8(xs[buf][tb * 32 + col][2 * j + g]);                     \
-                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b, acc[tb], 0, 0, 0);         \
+                const bf16x8 ah = as_bf16x8(xs[buf][0][tb * 32 + col][2 * j + g]);                  \
+                const bf16x8 al = as_bf16x8(xs[buf][1][tb * 32 + col][2 * j + g]);                  \
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc[tb], 0, 0, 0);         \
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc[tb], 0, 0, 0);         \
             }                                                                                       \
+            /* wide tiles: keep the compiler from hoisting all LDS reads (register pressure) */     \
+            if (TB > 2) __builtin_amdgcn_sched_barrier(0);                                          \
         }                                                                                           \
         if (k0 + GEMM_KC >= a.K || (i) == n_items - 1) {                                            \
             const int n = tile * BN + wave * 32 + col;                                              \
@@ -136,8 +151,9 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     }
 
     // prologue: items 0 .. ST-2 in flight (indices past the range are clamped: harmless reloads)
+    CATS_LOAD_X(0)
 #pragma unroll
-    for (int s = 0; s < ST - 1; ++s) CATS_LOAD_CHUNK(s, min(s, n_items - 1))
+    for (int s = 0; s < ST - 1; ++s) CATS_LOAD_W(s, min(s, n_items - 1))
 
     // Full groups of ST items whose refills all lie inside the range run without any
     // condition: a conditional step inside the loop would give the compiler a (never taken)
@@ -172,7 +188,8 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     }
 #undef CATS_TAIL
 #undef CATS_STEP
-#undef CATS_LOAD_CHUNK
+#undef CATS_LOAD_X
+#undef CATS_LOAD_W
 #undef CATS_ITEM
 }
 

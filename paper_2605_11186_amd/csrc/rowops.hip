@@ -64,12 +64,13 @@ __global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNorm
         const int j = 4 * tid + 4 * RN_THREADS * i;
         if (j < a.H) {
             const uint2 gbits = *reinterpret_cast<const uint2*>(a.gain + j);
-            uint2 o;
-            o.x = pack_bf2(v[i][0] * scale * __uint_as_float(gbits.x << 16),
-                           v[i][1] * scale * __uint_as_float(gbits.x & 0xFFFF0000u));
-            o.y = pack_bf2(v[i][2] * scale * __uint_as_float(gbits.y << 16),
-                           v[i][3] * scale * __uint_as_float(gbits.y & 0xFFFF0000u));
-            *reinterpret_cast<uint2*>(a.xn + row + j) = o;
+            uint2 hi, lo;
+            split_bf2(v[i][0] * scale * __uint_as_float(gbits.x << 16),
+                      v[i][1] * scale * __uint_as_float(gbits.x & 0xFFFF0000u), hi.x, lo.x);
+            split_bf2(v[i][2] * scale * __uint_as_float(gbits.y << 16),
+                      v[i][3] * scale * __uint_as_float(gbits.y & 0xFFFF0000u), hi.y, lo.y);
+            *reinterpret_cast<uint2*>(a.xn + row + j) = hi;
+            *reinterpret_cast<uint2*>(a.xn_lo + row + j) = lo;
         }
     }
 }
@@ -86,27 +87,37 @@ __global__ void cats_rope_table(RopeTableArgs a) {
     a.cs[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
 }
 
-// Adds up q|k|v partials, rotates q and k (pairs j, j+d/2), writes q, appends the
-// key row and the (transposed) value column of every node at cache row ctx_len + t.
-// grid (T, nh), block d/2.
+// Adds up q|k|v partials, rotates q and k (pairs j, j+d/2), writes q (high and low bf16
+// parts), appends the key row and the (transposed) value column of every node at cache row
+// ctx_len + t.  grid (T, nh), block d/2.
 __global__ void cats_qkv_rope_append(QkvRopeArgs a) {
     const int t = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
     const int half = a.d / 2;
     const int N = 3 * a.H;
-    float v6[6];
+    float v6[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int c0 = h * a.d + j;
-    v6[0] = sum_pieces(a.part, a.plan, a.T, N, t, c0);
-    v6[1] = sum_pieces(a.part, a.plan, a.T, N, t, c0 + half);
-    v6[2] = sum_pieces(a.part, a.plan, a.T, N, t, a.H + c0);
-    v6[3] = sum_pieces(a.part, a.plan, a.T, N, t, a.H + c0 + half);
-    v6[4] = sum_pieces(a.part, a.plan, a.T, N, t, 2 * a.H + c0);
-    v6[5] = sum_pieces(a.part, a.plan, a.T, N, t, 2 * a.H + c0 + half);
+    // the three column groups of one head lie in three different row tiles; within a head
+    // all columns share a tile (head_dim divides the tile height)
+#pragma unroll
+    for (int m = 0; m < 3; ++m) {
+        const int col = m * a.H + c0;
+        const int pieces = plan_pieces(a.plan, col / a.plan.bn);
+        const float* p = a.part + static_cast<size_t>(t) * N + col;
+        const size_t stride = static_cast<size_t>(a.T) * N;
+        for (int s = 0; s < pieces; ++s) {
+            v6[2 * m] += p[s * stride];
+            v6[2 * m + 1] += p[s * stride + half];
+        }
+    }
     const float2 cs = a.cs[t * half + j];
     const float q0 = v6[0] * cs.x - v6[1] * cs.y, q1 = v6[0] * cs.y + v6[1] * cs.x;
     const float k0 = v6[2] * cs.x - v6[3] * cs.y, k1 = v6[2] * cs.y + v6[3] * cs.x;
-    bf16_t* q = a.q + static_cast<size_t>(t) * a.H + h * a.d;
-    q[j] = f2bf(q0);
-    q[j + half] = f2bf(q1);
+    const size_t qo = static_cast<size_t>(t) * a.H + h * a.d;
+    const bf16_t q0h = f2bf(q0), q1h = f2bf(q1);
+    a.q[qo + j] = q0h;
+    a.q[qo + j + half] = q1h;
+    a.q_lo[qo + j] = f2bf(q0 - bf2f(q0h));
+    a.q_lo[qo + j + half] = f2bf(q1 - bf2f(q1h));
     const int row = a.ctx_len + t;
     bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + row) * a.d;
     k[j] = f2bf(k0);
@@ -116,14 +127,38 @@ __global__ void cats_qkv_rope_append(QkvRopeArgs a) {
     vt[static_cast<size_t>(j + half) * a.max_ctx] = f2bf(v6[5]);
 }
 
-// h[t][n] = silu(gate[t][n]) * up[t][n]
+// h[t][n] = silu(gate[t][n]) * up[t][n], two columns per thread, high and low bf16 parts
 __global__ void cats_swiglu(SwigluArgs a) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= a.T * a.F) return;
-    const int t = idx / a.F, n = idx - t * a.F;
-    const float gt = sum_pieces(a.part, a.plan, a.T, 2 * a.F, t, n);
-    const float up = sum_pieces(a.part, a.plan, a.T, 2 * a.F, t, a.F + n);
-    a.h[idx] = f2bf(gt / (1.0f + __expf(-gt)) * up);
+    const int half_f = a.F / 2;
+    if (idx >= a.T * half_f) return;
+    const int t = idx / half_f, n = 2 * (idx - t * half_f);
+    const int N = 2 * a.F;
+    float gt[2] = {0.f, 0.f}, up[2] = {0.f, 0.f};
+    const size_t stride = static_cast<size_t>(a.T) * N;
+    {
+        const int pieces = plan_pieces(a.plan, n / a.plan.bn);  // n even: n and n+1 share a tile
+        const float* p = a.part + static_cast<size_t>(t) * N + n;
+        for (int s = 0; s < pieces; ++s) {
+            const float2 v = *reinterpret_cast<const float2*>(p + s * stride);
+            gt[0] += v.x;
+            gt[1] += v.y;
+        }
+    }
+    {
+        const int pieces = plan_pieces(a.plan, (a.F + n) / a.plan.bn);
+        const float* p = a.part + static_cast<size_t>(t) * N + a.F + n;
+        for (int s = 0; s < pieces; ++s) {
+            const float2 v = *reinterpret_cast<const float2*>(p + s * stride);
+            up[0] += v.x;
+            up[1] += v.y;
+        }
+    }
+    uint32_t hi, lo;
+    split_bf2(gt[0] / (1.0f + __expf(-gt[0])) * up[0], gt[1] / (1.0f + __expf(-gt[1])) * up[1], hi, lo);
+    const size_t o = static_cast<size_t>(t) * a.F + n;
+    *reinterpret_cast<uint32_t*>(a.h + o) = hi;
+    *reinterpret_cast<uint32_t*>(a.h_lo + o) = lo;
 }
 
 // Per node: add up the logits partials, optionally store them, find the largest
@@ -190,7 +225,7 @@ void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st) {
 }
 
 void launch_swiglu(const SwigluArgs& a, hipStream_t st) {
-    const int n = a.T * a.F;
+    const int n = a.T * (a.F / 2);
     hipLaunchKernelGGL(cats_swiglu, dim3((n + 255) / 256), dim3(256), 0, st, a);
 }
 

@@ -1,0 +1,117 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The 7B-shaped 32-layer verify step (63-node top-k tree, KV context 1024) is run
+through the C ABI on the GPU and through the float32 oracle on the host, on the
+same seeded weights, context rows and tree.  Besides the whole-tensor comparison,
+sampled nodes are recomputed one by one by the oracle's plain token-at-a-time
+decoder over their own root-to-node paths.  Smaller-depth runs cover the 13B
+layer shape and the 128-node tree (the widest accumulator variant of the GEMM).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_11186_amd as cats
+import synth
+from gpu_common import MARGIN, REL_TOL, Pair, rel_err
+
+pytestmark = pytest.mark.gpu
+
+BENCH_SEED = 11186   # bench.py's default seed: the same weights, context and tree tokens
+
+
+def run_step(pair, ks, vs, S, tok, parent, depth):
+    T = len(parent)
+    d = pair.dims
+    hidden = torch.empty(T, d.hidden, dtype=torch.float32, device="cuda")
+    logits = torch.empty(T, d.vocab, dtype=torch.float32, device="cuda")
+    amax = torch.empty(T, dtype=torch.int32, device="cuda")
+    host = cats.AcceptResult()
+    cats.cats_set_tree(pair.ctx, tok, parent, depth)
+    cats.cats_verify_tree(pair.ctx, pair.layers_arr, 0, pair.L, pair.d_embed, None,
+                          pair.d_final["g_final"], pair.d_final["w_lm"], cats.kv_array(ks, vs), S,
+                          pair.res_dev, hidden_out=hidden, logits_out=logits, argmax_out=amax,
+                          out_host=host)
+    torch.cuda.synchronize()
+    return hidden.cpu().numpy(), logits.cpu().numpy(), amax.cpu().numpy(), host.as_dict()
+
+
+def compare_with_oracle(pair, S, tok, parent, depth, kv_seed, check_paths=()):
+    kc, vc = pair.oracle_cache_random(kv_seed, S)
+    ks, vs = pair.device_cache_from_oracle(kc, vc, S)
+    g_hidden, g_logits, g_amax, g_acc = run_step(pair, ks, vs, S, tok, parent, depth)
+    # definition-level spot checks first (they need the cache before the tree rows are written);
+    # the error of a node's row is measured on the scale of the whole tensor, like the full check
+    h_scale, l_scale = np.abs(g_hidden).max(), np.abs(g_logits).max()
+    for node in check_paths:
+        path = []
+        a = node
+        while a >= 0:
+            path.append(a)
+            a = int(parent[a])
+        path = path[::-1]
+        kc2, vc2 = kc.copy(), vc.copy()
+        x = pair.oracle.causal_decode(kc2, vc2, S, tokens=tok[path], layer_end=pair.L)
+        ref_logits = pair.oracle.lm_head(x[-1:])
+        e_h = np.abs(g_hidden[node] - x[-1]).max() / h_scale
+        e_l = np.abs(g_logits[node] - ref_logits[0]).max() / l_scale
+        print(f"node {node} (path length {len(path)}): hidden err {e_h:.3e}  logits err {e_l:.3e}")
+        assert e_h <= REL_TOL and e_l <= REL_TOL
+    o_hidden = pair.oracle.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=pair.L)
+    o_logits = pair.oracle.lm_head(o_hidden)
+    o_amax, o_margin = pair.oracle.argmax_margin(o_logits)
+    e_h, e_l = rel_err(g_hidden, o_hidden), rel_err(g_logits, o_logits)
+    print(f"hidden rel err {e_h:.3e}  logits rel err {e_l:.3e}  near-ties {(o_margin <= MARGIN).sum()}")
+    assert e_h <= REL_TOL and e_l <= REL_TOL
+    safe = o_margin > MARGIN
+    assert np.array_equal(g_amax[safe], o_amax[safe])
+    assert g_acc == pair.oracle.accept(tok, parent, depth, g_amax, S)
+    if safe.all():
+        assert g_acc == pair.oracle.accept(tok, parent, depth, o_amax, S)
+    pair.oracle.compact(kc, vc, S, g_acc["path"])
+    new_S = g_acc["new_ctx_len"]
+    for l in sorted({0, pair.L // 2, pair.L - 1}):
+        gk, gv = pair.device_rows(ks, vs, l, new_S)
+        assert rel_err(gk[S:], kc[l, S:new_S]) <= REL_TOL
+        assert rel_err(gv[S:], vc[l, S:new_S]) <= REL_TOL
+        assert np.array_equal(gk[:S], kc[l, :S].astype(np.float32))   # context rows untouched
+    return g_acc
+
+
+def test_7b_full_verify_step_matches_oracle():
+    dims = synth.V7B
+    parent, depth, _ = synth.product_tree_pruned()
+    T, S = len(parent), 1024
+    pair = Pair(dims, BENCH_SEED, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32")
+    try:
+        tok = synth.distinct_sibling_tokens(parent, dims.vocab, BENCH_SEED)
+        deep = int(np.flatnonzero(depth == 3)[0])
+        compare_with_oracle(pair, S, tok, parent, depth, BENCH_SEED, check_paths=(0, deep))
+    finally:
+        pair.close()
+
+
+def test_13b_layer_shape_three_layers():
+    dims = synth.V13B
+    parent, depth = synth.random_tree(64, 7, 4)
+    S = 2048
+    pair = Pair(dims, 13, max_ctx=2112, max_tree=64, precision="f32", n_layers=3)
+    try:
+        tok = synth.distinct_sibling_tokens(parent, dims.vocab, 13)
+        compare_with_oracle(pair, S, tok, parent, depth, 13)
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("T,S", [(128, 1024), (16, 512), (96, 4096)])
+def test_7b_layer_shape_tree_and_context_sweep(T, S):
+    """Tree sizes on both sides of the GEMM's accumulator variants and long contexts,
+    two 7B-shaped layers each."""
+    dims = synth.V7B
+    parent, depth = synth.random_tree(T, 8, T)
+    pair = Pair(dims, 7, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", n_layers=2)
+    try:
+        tok = synth.distinct_sibling_tokens(parent, dims.vocab, T)
+        compare_with_oracle(pair, S, tok, parent, depth, S)
+    finally:
+        pair.close()
