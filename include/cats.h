@@ -154,8 +154,8 @@ int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, const void *g_final,
 
 /* Measurement aid for the weight-streaming GEMM (the layer-weight pass of the
  * "Target verification pass"): while enabled, every GEMM launch made through
- * this context is bracketed by HIP events on its own stream (at most 1024
- * launches between two reads).  cats_profile_gemm_read waits for them and
+ * this context carries a pair of HIP events attached to its dispatch on its own
+ * stream (kernel begin / end; at most 1024 launches between two reads).  cats_profile_gemm_read waits for them and
  * returns the summed kernel time in milliseconds and the launch count (HOST
  * outputs), then starts a new collection. */
 int cats_profile_gemm(cats_ctx *ctx, int enable);

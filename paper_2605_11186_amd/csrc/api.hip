@@ -67,9 +67,9 @@ int target_wgs() {
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    // aim at ~512 waves per launch: heads * chunks * query groups
+    // aim at ~768 waves per launch (1024 SIMDs): heads * chunks * query groups
     const int tq = (c->T + 31) / 32;
-    int chunks = std::max(1, 512 / std::max(1, c->d.n_heads * tq));
+    int chunks = std::max(1, 768 / std::max(1, c->d.n_heads * tq));
     chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
     return (n_blocks + chunks - 1) / chunks;
 }
@@ -104,11 +104,11 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.T = c->T;
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
-    if (timed) (void)hipEventRecord(c->prof_ev[2 * c->prof_n], st);
-    launch_gemm(g, st);
     if (timed) {
-        (void)hipEventRecord(c->prof_ev[2 * c->prof_n + 1], st);
+        launch_gemm(g, st, c->prof_ev[2 * c->prof_n], c->prof_ev[2 * c->prof_n + 1]);
         ++c->prof_n;
+    } else {
+        launch_gemm(g, st);
     }
     return g.plan;
 }

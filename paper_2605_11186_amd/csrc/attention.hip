@@ -38,16 +38,16 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
     __syncthreads();
 
     // ancestor-or-self masks of this lane's two queries
-    uint32_t anc[2][4];
+    u32x4 anc[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        anc[qb][0] = anc[qb][1] = anc[qb][2] = anc[qb][3] = 0u;
+        anc[qb] = u32x4{0u, 0u, 0u, 0u};
         int node = qbase + 16 * qb + m;
         if (node >= T) node = -1;
         for (int step = 0; step <= CATS_MAX_DEPTH && node >= 0; ++step) {
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-                if ((node >> 5) == w) anc[qb][w] |= 1u << (node & 31);
+            const uint32_t bit = 1u << (node & 31);
+            const int w = node >> 5;
+            anc[qb] |= u32x4{w == 0 ? bit : 0u, w == 1 ? bit : 0u, w == 2 ? bit : 0u, w == 3 ? bit : 0u};
             node = s_parent[node];
         }
     }
@@ -87,11 +87,11 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
     const int blk_begin = chunk * a.blocks_per_chunk;
     const int blk_end = min(n_blocks, blk_begin + a.blocks_per_chunk);
 
-    for (int blk = blk_begin; blk < blk_end; ++blk) {
+    // The K / V fragments of one 32-key block.  Score-block rows are permuted so that a lane
+    // ends up with 8 consecutive keys: sub-block b, MFMA row mm <-> key j0 + 8*(mm/4) + 4*b + mm%4.
+    // V^T fragments: row = dim, k = 8 consecutive keys starting at j0 + 8*q4.
+    auto load_block = [&](bf16x8 (&kf)[2][KS], bf16x8 (&vf)[DB], int blk) {
         const int j0 = blk * ATTN_KB;
-        // score block rows are permuted so that a lane ends up with 8 consecutive keys:
-        // sub-block b, MFMA row mm  <->  key j0 + 8*(mm/4) + 4*b + mm%4
-        bf16x8 kf[2][KS];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
             const int key = j0 + 8 * (m >> 2) + 4 * b + (m & 3);
@@ -100,13 +100,20 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
                 kf[b][s] = as_bf16x8(*reinterpret_cast<const u32x4*>(
                     kbase + static_cast<size_t>(key) * D + 32 * s + 8 * q4));
         }
-        // V^T fragments: row = dim, k = 8 consecutive keys starting at j0 + 8*q4
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+            vf[db] = as_bf16x8(*reinterpret_cast<const u32x4*>(
+                vbase + static_cast<size_t>(16 * db + m) * a.max_ctx + j0 + 8 * q4));
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    auto compute_block = [&](const bf16x8 (&kf)[2][KS], const bf16x8 (&vf_in)[DB], int blk) {
+        const int j0 = blk * ATTN_KB;
         const int key0 = j0 + 8 * q4;
         bf16x8 vf[DB];
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-            u32x4 v = *reinterpret_cast<const u32x4*>(
-                vbase + static_cast<size_t>(16 * db + m) * a.max_ctx + key0);
+            u32x4 v = __builtin_bit_cast(u32x4, vf_in[db]);
             if (key0 + 8 > n_keys) {  // rows past the tree may hold anything: zero them
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -116,7 +123,6 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
             }
             vf[db] = as_bf16x8(v);
         }
-
         const bool all_ctx = j0 + ATTN_KB <= S;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -142,10 +148,9 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
                     const int rel = key - S;
                     v = rel < 0;
                     if (rel >= 0 && rel < T) {
-                        uint32_t word = anc[qb][0];
-#pragma unroll
-                        for (int w = 1; w < 4; ++w)
-                            if ((rel >> 5) == w) word = anc[qb][w];
+                        const int w = rel >> 5;
+                        const u32x4 am = anc[qb];
+                        const uint32_t word = w == 0 ? am[0] : (w == 1 ? am[1] : (w == 2 ? am[2] : am[3]));
                         v = (word >> (rel & 31)) & 1u;
                     }
                 }
@@ -181,6 +186,21 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
                 o[qb][db] *= alpha;
                 o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[qb][db], 0, 0, 0);
                 o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pfl, o[qb][db], 0, 0, 0);
+            }
+        }
+    };
+
+    // Two register sets: the fragments of block b+1 are requested before block b is
+    // multiplied, so the cache latency of one block hides behind the arithmetic of the other.
+    bf16x8 kfA[2][KS], kfB[2][KS], vfA[DB], vfB[DB];
+    if (blk_begin < blk_end) {
+        load_block(kfA, vfA, blk_begin);
+        for (int blk = blk_begin; blk < blk_end; blk += 2) {
+            load_block(kfB, vfB, min(blk + 1, blk_end - 1));
+            compute_block(kfA, vfA, blk);
+            if (blk + 1 < blk_end) {
+                load_block(kfA, vfA, min(blk + 2, blk_end - 1));
+                compute_block(kfB, vfB, blk + 1);
             }
         }
     }

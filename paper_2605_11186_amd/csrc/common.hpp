@@ -85,7 +85,7 @@ constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
 constexpr int GEMM_ST4 = CATS_GEMM_ST4;  // ... for T > 64 (larger accumulators)
 GemmPlan make_gemm_plan(int N, int K, int target_wgs);
 int gemm_plan_max_pieces(const GemmPlan& p);
-void launch_gemm(const GemmArgs& a, hipStream_t st);
+void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // Sum of the pieces of column n of row t (fixed order).
 __device__ __forceinline__ float sum_pieces(const float* part, const GemmPlan& p, int T, int N, int t, int n) {

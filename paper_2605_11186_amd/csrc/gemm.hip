@@ -13,6 +13,8 @@
 // its range without a break (the ring keeps prefetching across tile boundaries) and
 // writes one float32 partial tile ("piece") for every tile it touches.  The following
 // epilogue kernel adds a tile's pieces in a fixed order.
+#include <hip/hip_ext.h>
+
 #include "common.hpp"
 
 namespace {
@@ -215,14 +217,19 @@ int gemm_plan_max_pieces(const GemmPlan& p) {
     return m;
 }
 
-void launch_gemm(const GemmArgs& a, hipStream_t st) {
+// With events given, they are attached to the dispatch itself (kernel begin / end
+// timestamps), so the elapsed time is the kernel's execution time without launch latency.
+void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     constexpr int NW = GEMM_BN / 32;
-    dim3 grid(a.plan.n_wgs);
+    const dim3 grid(a.plan.n_wgs), block(64 * NW);
     const int tb = (a.T + 31) / 32;
+#define CATS_LAUNCH(TBV, STV)                                                                         \
+    hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV>), grid, block, 0, st, ev_start, ev_stop, 0, a)
     switch (tb) {
-        case 1: hipLaunchKernelGGL((cats_gemm_skinny_bf16<1, NW, GEMM_ST>), grid, dim3(64 * NW), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((cats_gemm_skinny_bf16<2, NW, GEMM_ST>), grid, dim3(64 * NW), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((cats_gemm_skinny_bf16<3, NW, GEMM_ST4>), grid, dim3(64 * NW), 0, st, a); break;
-        default: hipLaunchKernelGGL((cats_gemm_skinny_bf16<4, NW, GEMM_ST4>), grid, dim3(64 * NW), 0, st, a); break;
+        case 1: CATS_LAUNCH(1, GEMM_ST); break;
+        case 2: CATS_LAUNCH(2, GEMM_ST); break;
+        case 3: CATS_LAUNCH(3, GEMM_ST4); break;
+        default: CATS_LAUNCH(4, GEMM_ST4); break;
     }
+#undef CATS_LAUNCH
 }
