@@ -30,6 +30,10 @@ WORKLOADS = {
     "7b_t63_s1024": dict(model="V7B", ctx=1024, tree="topk63", label="Vicuna-7B-shaped (32L, H4096, F11008, V32000) verify step, 63-node top-k tree (4/3/2/2/1/1 pruned), KV context 1024"),
     "7b_t64_s1024": dict(model="V7B", ctx=1024, tree="rand64", label="7B-shape, 64-node random tree (depth<=8), KV context 1024"),
     "13b_t64_s2048": dict(model="V13B", ctx=2048, tree="rand64d7", label="13B-shape (40L, H5120, F13824), 64-node tree (depth 7), KV context 2048"),
+    # BASELINE configs[4]: offload regime, weights streamed from pinned host memory
+    "7b_offload_t128_s1024": dict(model="V7B", ctx=1024, tree="rand128", offload=True, label="7B-shape, layer weights in pinned host memory streamed through two HBM staging buffers, 128-node random tree, KV context 1024"),
+    # BASELINE configs[3]: 100 consecutive verify-accept-compact iterations
+    "13b_t64_s2048_x100": dict(model="V13B", ctx=2048, tree="rand64d7", iterate=100, label="13B-shape (40L, H5120, F13824), 100 verify-accept-compact iterations, 64-node trees (depth 7), KV context from 2048"),
     "tiny": dict(model="TINY", ctx=128, tree="binary15", label="tiny oracle-check model, 15-node binary tree, KV context 128"),
 }
 
@@ -56,6 +60,72 @@ def algorithmic_bytes(dims, T, S, n_layers):
     w_lm = dims.vocab * dims.hidden * 2
     kv = n_layers * 2 * (S + T) * dims.hidden * 2
     return w_layers + w_lm, kv
+
+
+def run_iterations(args, wl, dims, cats, synth, torch, np, ctx, layers_arr, kv_arr, d_embed, d_final, res_dev,
+                   stream, S0, n_iter, seed):
+    """Consecutive verify-accept-compact iterations on a seeded token stream: a reference greedy
+    stream is first produced by the same library with root-only trees (plain decoding); every
+    iteration then verifies a fresh tree whose first child at each level carries the true next
+    token with probability 0.8, and the committed stream must reproduce the reference."""
+    L = dims.n_layers
+    rng = np.random.default_rng(seed)
+    host = cats.AcceptResult()
+    one = (np.array([-1], np.int32), np.array([0], np.int32))
+
+    def verify(tok, parent, depth, S):
+        cats.cats_set_tree(ctx, tok, parent, depth, stream)
+        cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"], d_final["w_lm"],
+                              kv_arr, S, res_dev, out_host=host, stream=stream)
+        return host.as_dict()
+
+    n_ref = n_iter * 8 + 16
+    ref, tok, S = [], int(rng.integers(dims.vocab)), S0
+    first = tok
+    t0 = time.perf_counter()
+    for _ in range(n_ref):
+        r = verify(np.array([tok], np.int32), one[0], one[1], S)
+        tok = r["bonus_token"]
+        ref.append(tok)
+        S += 1
+    t_ref = time.perf_counter() - t0
+    # the K/V rows written above stay valid for the speculative run: it starts from S0 again
+    committed, S, root = [], S0, first
+    accepted = []
+    t0 = time.perf_counter()
+    for it in range(n_iter):
+        parent, depth = synth.random_tree(64, 7, seed + it)
+        T = len(parent)
+        tok_arr = np.zeros(T, np.int32)
+        tok_arr[0] = root
+        first_child = {}
+        for i in range(1, T):
+            p = int(parent[i])
+            want = ref[len(committed) + depth[i] - 1]
+            sib = first_child.setdefault(p, set())
+            t = want if (not sib and rng.random() < 0.8) else int(rng.integers(dims.vocab))
+            while t in sib:
+                t = int(rng.integers(dims.vocab))
+            sib.add(t)
+            tok_arr[i] = t
+        r = verify(tok_arr, parent, depth, S)
+        committed += r["tokens"][1:] + [r["bonus_token"]]
+        accepted.append(r["n_accepted"])
+        S, root = r["new_ctx_len"], r["bonus_token"]
+    elapsed = time.perf_counter() - t0
+    n = len(committed)
+    mismatch = next((i for i in range(n) if committed[i] != ref[i]), None)
+    return {"metric": "tree-verify steps/sec", "value": round(n_iter / elapsed, 3), "unit": "steps/s",
+            "n_gpus": 1, "steps": n_iter, "warmup": 0, "ms_per_step": round(elapsed / n_iter * 1e3, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+            "data": "synthetic",
+            "config": {"workload": wl["label"], "key": args.workload, "tree_nodes": 64, "ctx_len": S0,
+                       "layers": L, "seed": seed},
+            "iterations": {"mean_accepted": round(float(np.mean(accepted)), 3),
+                           "tokens_committed": n, "tokens_per_s": round(n / elapsed, 1),
+                           "plain_decode_tokens_per_s": round(n_ref / t_ref, 1),
+                           "first_mismatch_vs_plain_greedy": mismatch,
+                           "note": "each step ends with a host read-back of the accept result"}}
 
 
 def main():
@@ -95,7 +165,9 @@ def main():
     T = len(parent)
     L = dims.n_layers
     seed = args.seed
-    max_ctx = (S + T + 63) // 64 * 64
+    iterate = wl.get("iterate", 0)
+    offload = wl.get("offload", False)
+    max_ctx = (S + T + (iterate * 9 if iterate else 0) + 63) // 64 * 64
     tok = synth.distinct_sibling_tokens(parent, dims.vocab, seed)
 
     dev = torch.device("cuda:0")
@@ -106,9 +178,13 @@ def main():
     host_layers = []   # kept only for the CPU-baseline sample
     d_layers = []
     n_keep = 0 if args.no_cpu_baseline else min(args.cpu_sample_layers, L)
+    pinned_layers = []  # offload regime: the weights stay in pinned host memory
     for l in range(L):
         w = synth.layer_weights(dims, seed, l)
-        d_layers.append({k: to_dev(v) for k, v in w.items()})
+        if offload:
+            pinned_layers.append({k: torch.from_numpy(v.view(np.int16)).pin_memory() for k, v in w.items()})
+        else:
+            d_layers.append({k: to_dev(v) for k, v in w.items()})
         if l < n_keep:
             host_layers.append(w)
     final = synth.final_weights(dims, seed)
@@ -128,15 +204,29 @@ def main():
     desc = cats.ModelDesc(L, dims.hidden, dims.n_heads, dims.head_dim, dims.ffn, dims.vocab, max_ctx,
                           max(T, 1), dims.rms_eps, dims.rope_base)
     ctx = cats.cats_create(desc)
-    layers_arr = cats.layer_array(d_layers)
+    layers_arr = cats.layer_array(pinned_layers if offload else d_layers)
     kv_arr = cats.kv_array(ks, vs)
+    if offload:
+        layer_bytes = cats.cats_layer_weight_bytes(desc)
+        staging = [torch.empty(layer_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
     res_dev = cats.accept_result_tensor(dev)
     stream = torch.cuda.current_stream()
 
     def step():
         cats.cats_set_tree(ctx, tok, parent, depth, stream)
-        cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"], d_final["w_lm"],
-                              kv_arr, S, res_dev, stream=stream)
+        if offload:
+            cats.cats_verify_tree_streamed(ctx, layers_arr, 0, L, staging, d_embed, None, d_final["g_final"],
+                                           d_final["w_lm"], kv_arr, S, res_dev, stream=stream)
+        else:
+            cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"], d_final["w_lm"],
+                                  kv_arr, S, res_dev, stream=stream)
+
+    if iterate:
+        out = run_iterations(args, wl, dims, cats, synth, torch, np, ctx, layers_arr, kv_arr, d_embed, d_final,
+                             res_dev, stream, S, iterate, seed)
+        cats.cats_destroy(ctx)
+        print(json.dumps(out))
+        return
 
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -200,6 +290,27 @@ def main():
         "input_generation_s": round(gen_s, 1),
     }
 
+    if offload:
+        # copy alone (same pinned tensors, same staging buffers) and compute alone (two layers kept
+        # resident, scaled) bound the overlap: hidden = how much of the shorter leg disappears
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for w in pinned_layers:
+            off = 0
+            buf = staging[0]
+            for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn"):
+                n = w[k].numel() * 2
+                buf[off:off + n].view(torch.int16).view(w[k].shape).copy_(w[k], non_blocking=True)
+                off += n
+        torch.cuda.synchronize()
+        t_copy = time.perf_counter() - t1
+        t_step = ms_per_step * 1e-3
+        out["offload"] = {"link_gbs": round(w_bytes / t_step / 1e9, 2),
+                          "copy_only_s": round(t_copy, 4), "step_s": round(t_step, 4),
+                          "copy_link_gbs": round((w_bytes - dims.vocab * dims.hidden * 2) / t_copy / 1e9, 2),
+                          "gemm_compute_s_per_step": round(gemm_ms * 1e-3 / args.steps, 5),
+                          "exposed_beyond_copy_s": round(max(0.0, t_step - t_copy), 5)}
+        out["roofline"]["note"] = "offload regime: the step is bound by the host link, not by HBM"
     if not args.no_cpu_baseline:
         from oracle.cats_oracle import Oracle
         orc = Oracle(dims, host_layers + [None] * (L - n_keep), final, embed, precision="f32")

@@ -147,6 +147,23 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
                      float *margin_out, cats_accept_result *out_dev, cats_accept_result *out_host,
                      void *stream);
 
+/* Offload regime (Sec. 3.2: the target layers are "streamed ... chunk by chunk" while the
+ * previous chunk computes; Fig. 4 left): the same verify step with the layer weights held
+ * in pinned HOST memory.  host_layers: HOST array indexed by layer whose nine pointers are
+ * pinned HOST addresses.  staging[0..1]: two DEVICE buffers of cats_layer_weight_bytes()
+ * each; layer l is copied into staging[l & 1] on the context's own copy stream while layer
+ * l-1 computes on `stream` (events order the two streams; the copy of layer l+2 waits until
+ * layer l has been consumed).  Everything else is as in cats_verify_tree (embed, g_final and
+ * w_lm are DEVICE pointers).  The call returns after enqueueing unless out_host is given. */
+size_t cats_layer_weight_bytes(const cats_model_desc *desc);
+int cats_verify_tree_streamed(cats_ctx *ctx, const cats_layer_weights *host_layers,
+                              int32_t layer_begin, int32_t layer_end, void *const staging[2],
+                              const void *embed, const float *hidden_in, const void *g_final,
+                              const void *w_lm, const cats_kv_layer *kv, int32_t ctx_len,
+                              float *hidden_out, float *logits_out, int32_t *argmax_out,
+                              float *margin_out, cats_accept_result *out_dev,
+                              cats_accept_result *out_host, void *stream);
+
 /* Final RMSNorm + LM head + argmax alone (Algorithm 1: p_tgt = softmax(H(H_tgt));
  * greedy acceptance needs only the argmax).  hidden: float32 [T][hidden]. */
 int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, const void *g_final, const void *w_lm,

@@ -16,7 +16,7 @@ __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWe
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
            "cats_accept_and_compact", "cats_verify_tree", "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
-           "layer_weights_struct", "kv_array",
+           "cats_verify_tree_streamed", "cats_layer_weight_bytes", "layer_weights_struct", "kv_array",
            "layer_array", "kv_from_rows", "kv_to_rows", "accept_result_tensor",
            "accept_result_from_tensor", "CATS_OK", "CATS_EINVAL", "CATS_ECAPACITY", "CATS_ESTATE",
            "CATS_EHIP"]
@@ -79,6 +79,10 @@ _SIGNATURES = {
     "cats_verify_tree": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_verify_tree_streamed": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -92,7 +96,8 @@ def library_path() -> Path:
 
 def exported_symbols():
     """Names every build must export (those declared in include/cats.h)."""
-    return sorted(list(_SIGNATURES) + ["cats_gemm_kernel_name", "cats_strerror"])
+    return sorted(list(_SIGNATURES) + ["cats_gemm_kernel_name", "cats_strerror",
+                                       "cats_layer_weight_bytes"])
 
 
 def library():
@@ -110,6 +115,8 @@ def library():
             fn.restype = C.c_int
         lib.cats_strerror.argtypes = [C.c_int]
         lib.cats_strerror.restype = C.c_char_p
+        lib.cats_layer_weight_bytes.argtypes = [C.c_void_p]
+        lib.cats_layer_weight_bytes.restype = C.c_size_t
         lib.cats_gemm_kernel_name.argtypes = []
         lib.cats_gemm_kernel_name.restype = C.c_char_p
         _lib = lib
@@ -198,6 +205,24 @@ def cats_verify_tree(ctx, layers_arr, layer_begin: int, layer_end: int, embed, h
         _dp(w_lm), kv_arr, int(ctx_len), _dp(hidden_out), _dp(logits_out), _dp(argmax_out),
         _dp(margin_out), _dp(out_dev), None if out_host is None else C.byref(out_host),
         _stream(stream)))
+
+
+def cats_layer_weight_bytes(desc: ModelDesc) -> int:
+    return int(library().cats_layer_weight_bytes(C.byref(desc)))
+
+
+def cats_verify_tree_streamed(ctx, host_layers_arr, layer_begin: int, layer_end: int, staging, embed,
+                              hidden_in, g_final, w_lm, kv_arr, ctx_len: int, out_dev, hidden_out=None,
+                              logits_out=None, argmax_out=None, margin_out=None,
+                              out_host: AcceptResult | None = None, stream=None):
+    """`host_layers_arr`: LayerWeights array whose pointers are pinned host addresses;
+    `staging`: two device tensors of cats_layer_weight_bytes() bytes each."""
+    stg = (C.c_void_p * 2)(staging[0].data_ptr(), staging[1].data_ptr())
+    _check(library().cats_verify_tree_streamed(
+        ctx, host_layers_arr, int(layer_begin), int(layer_end), stg, _dp(embed), _dp(hidden_in),
+        _dp(g_final), _dp(w_lm), kv_arr, int(ctx_len), _dp(hidden_out), _dp(logits_out),
+        _dp(argmax_out), _dp(margin_out), _dp(out_dev),
+        None if out_host is None else C.byref(out_host), _stream(stream)))
 
 
 def cats_lm_head_argmax(ctx, hidden, g_final, w_lm, argmax_out, logits_out=None, margin_out=None,

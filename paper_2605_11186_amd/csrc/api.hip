@@ -32,6 +32,9 @@ struct cats_ctx {
     int attn_max_chunks;
     int32_t* amax;   // [max_tree]
     char* flat;      // the single allocation behind all of the above
+    // offload regime: copy stream and the events that order it against the compute stream
+    hipStream_t copy_stream;
+    hipEvent_t ev_copied[2], ev_consumed[2];
     // optional timing of the weight-streaming GEMM launches (measurement aid)
     bool prof_on;
     int prof_n;
@@ -67,9 +70,9 @@ int target_wgs() {
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    // aim at ~768 waves per launch (1024 SIMDs): heads * chunks * query groups
+    // aim at ~512 waves per launch (1024 SIMDs): heads * chunks * query groups
     const int tq = (c->T + 31) / 32;
-    int chunks = std::max(1, 768 / std::max(1, c->d.n_heads * tq));
+    int chunks = std::max(1, 512 / std::max(1, c->d.n_heads * tq));
     chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
     return (n_blocks + chunks - 1) / chunks;
 }
@@ -268,6 +271,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     if (!c) return CATS_EHIP;
     c->d = d;
     c->T = 0;
+    c->copy_stream = nullptr;
+    for (int i = 0; i < 2; ++i) c->ev_copied[i] = c->ev_consumed[i] = nullptr;
     c->prof_on = false;
     c->prof_n = 0;
     for (auto& e : c->prof_ev) e = nullptr;
@@ -339,6 +344,11 @@ int cats_destroy(cats_ctx* ctx) {
     if (!ctx) return CATS_EINVAL;
     for (auto& ev : ctx->prof_ev)
         if (ev) (void)hipEventDestroy(ev);
+    for (int i = 0; i < 2; ++i) {
+        if (ctx->ev_copied[i]) (void)hipEventDestroy(ctx->ev_copied[i]);
+        if (ctx->ev_consumed[i]) (void)hipEventDestroy(ctx->ev_consumed[i]);
+    }
+    if (ctx->copy_stream) (void)hipStreamDestroy(ctx->copy_stream);
     hipError_t e = hipFree(ctx->flat);
     delete ctx;
     return e == hipSuccess ? CATS_OK : hip_fail(e);
@@ -511,6 +521,110 @@ int cats_profile_gemm_read(cats_ctx* ctx, float* total_ms, int32_t* launches) {
     *launches = ctx->prof_n;
     ctx->prof_n = 0;
     return CATS_OK;
+}
+
+size_t cats_layer_weight_bytes(const cats_model_desc* desc) {
+    if (!desc) return 0;
+    const size_t H = desc->hidden, F = desc->ffn;
+    return (4 * H * H + 3 * H * F + 2 * H) * sizeof(bf16_t);
+}
+
+int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_layers, int32_t layer_begin,
+                              int32_t layer_end, void* const staging[2], const void* embed,
+                              const float* hidden_in, const void* g_final, const void* w_lm,
+                              const cats_kv_layer* kv, int32_t ctx_len, float* hidden_out, float* logits_out,
+                              int32_t* argmax_out, float* margin_out, cats_accept_result* out_dev,
+                              cats_accept_result* out_host, void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (layer_begin < 0 || layer_end <= layer_begin || layer_end > ctx->d.n_layers) return CATS_EINVAL;
+    if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;
+    if (!g_final || !w_lm || !out_dev || !host_layers || !staging || !staging[0] || !staging[1] ||
+        !kv_ok(kv, layer_begin, layer_end))
+        return CATS_EINVAL;
+    for (int l = layer_begin; l < layer_end; ++l)
+        if (!layer_ok(&host_layers[l])) return CATS_EINVAL;
+    if (!ctx->copy_stream) {  // created on first use, at the default priority
+        HIP_TRY(hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 2; ++i) {
+            HIP_TRY(hipEventCreateWithFlags(&ctx->ev_copied[i], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&ctx->ev_consumed[i], hipEventDisableTiming));
+        }
+    }
+    hipStream_t st = as_stream(stream), cs = ctx->copy_stream;
+    const size_t H = ctx->d.hidden, F = ctx->d.ffn;
+    const int T = ctx->T;
+    // layout of one staged layer: wq | wk | wv | wo | w_gate | w_up | w_down | g_attn | g_ffn
+    const size_t sizes[9] = {H * H, H * H, H * H, H * H, F * H, F * H, H * F, H, H};
+    auto staged = [&](int b) {
+        cats_layer_weights w;
+        const void** fields[9] = {&w.wq, &w.wk, &w.wv, &w.wo, &w.w_gate, &w.w_up, &w.w_down, &w.g_attn, &w.g_ffn};
+        char* p = static_cast<char*>(staging[b]);
+        for (int i = 0; i < 9; ++i) {
+            *fields[i] = p;
+            p += sizes[i] * sizeof(bf16_t);
+        }
+        return w;
+    };
+    auto enqueue_copy = [&](int l, bool wait_consumed) -> int {
+        const int b = (l - layer_begin) & 1;
+        if (wait_consumed) HIP_TRY(hipStreamWaitEvent(cs, ctx->ev_consumed[b], 0));
+        const cats_layer_weights& hw = host_layers[l];
+        const void* src[9] = {hw.wq, hw.wk, hw.wv, hw.wo, hw.w_gate, hw.w_up, hw.w_down, hw.g_attn, hw.g_ffn};
+        char* p = static_cast<char*>(staging[b]);
+        for (int i = 0; i < 9; ++i) {
+            HIP_TRY(hipMemcpyAsync(p, src[i], sizes[i] * sizeof(bf16_t), hipMemcpyHostToDevice, cs));
+            p += sizes[i] * sizeof(bf16_t);
+        }
+        HIP_TRY(hipEventRecord(ctx->ev_copied[b], cs));
+        return CATS_OK;
+    };
+
+    // the copy stream must not overtake work already queued on the compute stream that may
+    // still read the staging buffers (a previous call): order it behind that work once
+    HIP_TRY(hipEventRecord(ctx->ev_consumed[0], st));
+    HIP_TRY(hipStreamWaitEvent(cs, ctx->ev_consumed[0], 0));
+    int erc = enqueue_copy(layer_begin, false);
+    if (erc != CATS_OK) return erc;
+
+    enqueue_rope_table(ctx, ctx_len, st);
+    ResidualNormArgs rn;
+    rn.x = ctx->x;
+    rn.x_in = hidden_in;
+    rn.embed = static_cast<const bf16_t*>(embed);
+    rn.token = ctx->token;
+    rn.part = nullptr;
+    rn.plan = GemmPlan{1, 1, 1, 1};
+    rn.gain = nullptr;  // input rows only; each layer's first norm is launched once its gains have arrived
+    rn.xn = ctx->xn;
+    rn.xn_lo = ctx->xn_lo;
+    rn.T = T;
+    rn.H = ctx->d.hidden;
+    rn.eps = ctx->d.rms_eps;
+    launch_residual_norm(rn, st);
+    rn.x_in = nullptr;
+    rn.embed = nullptr;
+    for (int l = layer_begin; l < layer_end; ++l) {
+        const int b = (l - layer_begin) & 1;
+        if (l + 1 < layer_end) {
+            erc = enqueue_copy(l + 1, l + 1 - layer_begin >= 2);
+            if (erc != CATS_OK) return erc;
+        }
+        HIP_TRY(hipStreamWaitEvent(st, ctx->ev_copied[b], 0));
+        const cats_layer_weights w = staged(b);
+        rn.gain = static_cast<const bf16_t*>(w.g_attn);
+        launch_residual_norm(rn, st);
+        enqueue_layer(ctx, &w, ctx->x, &kv[l], ctx_len, nullptr, st);
+        HIP_TRY(hipEventRecord(ctx->ev_consumed[b], st));
+    }
+    rn.gain = static_cast<const bf16_t*>(g_final);
+    launch_residual_norm(rn, st);
+    if (hidden_out)
+        HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
+    int32_t* amax = argmax_out ? argmax_out : ctx->amax;
+    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
+    HIP_TRY(hipGetLastError());
+    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
 }
 
 const char* cats_gemm_kernel_name(void) { return "cats_gemm_skinny_bf16"; }

@@ -342,3 +342,46 @@ def test_error_codes_from_host_validation(tiny):
     cats.cats_destroy(fresh)
     with pytest.raises(cats.CatsError):
         cats.cats_create(cats.ModelDesc(2, 250, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0))
+
+
+def test_streamed_weights_give_the_same_step(tiny):
+    """Offload regime: layer weights in pinned host memory, copied through two staging buffers
+    while the previous layer computes.  Same kernels on the same values: results are identical
+    to the resident call, bit for bit."""
+    d = synth.TINY
+    parent, depth = synth.random_tree(40, 6, 11)
+    tok = synth.distinct_sibling_tokens(parent, d.vocab, 11)
+    T, S = len(parent), 96
+    kc, vc = tiny.oracle_cache_random(77, S)
+    outs = []
+    desc = cats.ModelDesc(d.n_layers, d.hidden, d.n_heads, d.head_dim, d.ffn, d.vocab, tiny.max_ctx, 128,
+                          d.rms_eps, d.rope_base)
+    nbytes = cats.cats_layer_weight_bytes(desc)
+    assert nbytes == d.layer_weight_elems() * 2
+    host_layers = [{k: torch.from_numpy(v.view(np.int16).copy()).pin_memory() for k, v in w.items()}
+                   for w in tiny.layers]
+    staging = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for streamed in (False, True, True):
+        ks, vs = tiny.device_cache_from_oracle(kc, vc, S)
+        hidden = torch.empty(T, d.hidden, dtype=torch.float32, device="cuda")
+        logits = torch.empty(T, d.vocab, dtype=torch.float32, device="cuda")
+        host = cats.AcceptResult()
+        cats.cats_set_tree(tiny.ctx, tok, parent, depth)
+        common = dict(hidden_out=hidden, logits_out=logits, out_host=host)
+        if streamed:
+            cats.cats_verify_tree_streamed(tiny.ctx, cats.layer_array(host_layers), 0, tiny.L, staging,
+                                           tiny.d_embed, None, tiny.d_final["g_final"], tiny.d_final["w_lm"],
+                                           cats.kv_array(ks, vs), S, tiny.res_dev, **common)
+        else:
+            cats.cats_verify_tree(tiny.ctx, tiny.layers_arr, 0, tiny.L, tiny.d_embed, None,
+                                  tiny.d_final["g_final"], tiny.d_final["w_lm"], cats.kv_array(ks, vs), S,
+                                  tiny.res_dev, **common)
+        torch.cuda.synchronize()
+        outs.append((hidden.cpu(), logits.cpu(), host.as_dict(), [k.cpu() for k in ks]))
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1]) and o[2] == outs[0][2]
+        new_S = o[2]["new_ctx_len"]
+        assert all(torch.equal(a[:, :new_S], b[:, :new_S]) for a, b in zip(o[3], outs[0][3]))
+    # and against the oracle
+    o_hidden = tiny.oracle.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=tiny.L)
+    assert rel_err(outs[1][0].numpy(), o_hidden) <= REL_TOL
