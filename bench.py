@@ -264,6 +264,14 @@ def main():
     gemm_gbs = gemm_bytes_per_launch / gemm_avg_s / 1e9
     step_gbs = (w_bytes + kv_bytes) / (ms_per_step * 1e-3) / 1e9
 
+    # HBM traffic per GEMM launch from the committed rocprofv3 --pmc summary of this same workload
+    traffic = None
+    prof = ROOT / "profiles" / f"cats_gemm_{args.workload}.pmc.txt"
+    if prof.exists() and not args.tree_nodes and not args.ctx:
+        for line in prof.read_text().splitlines():
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
+
     out = {
         "metric": "tree-verify steps/sec",
         "value": round(1e3 / ms_per_step, 3),
@@ -283,7 +291,7 @@ def main():
                      "achieved_gbs": round(step_gbs, 1), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": cats.cats_gemm_kernel_name(),
                      "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "launches_per_step": gemm_launches // args.steps,
                      "avg_launch_us": round(gemm_avg_s * 1e6, 2),
                      "bytes_per_launch": int(gemm_bytes_per_launch)},
