@@ -181,15 +181,17 @@ def main():
     pinned_layers = []  # offload regime: the weights stay in pinned host memory
     for l in range(L):
         w = synth.layer_weights(dims, seed, l)
+        dw = cats.pack_layer({k: to_dev(v) for k, v in w.items()})   # one-time re-tiling, row-major copy dropped
         if offload:
-            pinned_layers.append({k: torch.from_numpy(v.view(np.int16)).pin_memory() for k, v in w.items()})
+            pinned_layers.append({k: v.view(torch.int16).cpu().pin_memory() for k, v in dw.items()})
         else:
-            d_layers.append({k: to_dev(v) for k, v in w.items()})
+            d_layers.append(dw)
         if l < n_keep:
             host_layers.append(w)
     final = synth.final_weights(dims, seed)
     embed = synth.embedding(dims, seed)
     d_final = {k: to_dev(v) for k, v in final.items()}
+    d_final["w_lm"] = cats.cats_pack_matrix(d_final["w_lm"])
     d_embed = to_dev(embed)
     ks, vs, host_kv = [], [], []
     for l in range(L):
@@ -202,7 +204,7 @@ def main():
     gen_s = time.time() - t0
 
     desc = cats.ModelDesc(L, dims.hidden, dims.n_heads, dims.head_dim, dims.ffn, dims.vocab, max_ctx,
-                          max(T, 1), dims.rms_eps, dims.rope_base)
+                          max(T, 1), dims.rms_eps, dims.rope_base, 1)
     ctx = cats.cats_create(desc)
     layers_arr = cats.layer_array(pinned_layers if offload else d_layers)
     kv_arr = cats.kv_array(ks, vs)
@@ -308,7 +310,7 @@ def main():
             buf = staging[0]
             for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "g_attn", "g_ffn"):
                 n = w[k].numel() * 2
-                buf[off:off + n].view(torch.int16).view(w[k].shape).copy_(w[k], non_blocking=True)
+                buf[off:off + n].view(torch.int16).copy_(w[k].reshape(-1), non_blocking=True)
                 off += n
         torch.cuda.synchronize()
         t_copy = time.perf_counter() - t1

@@ -58,10 +58,13 @@ typedef struct {
     int32_t max_ctx;  /* rows each KV cache holds                         */
     int32_t max_tree; /* largest T this context will be asked to verify   */
     float rms_eps, rope_base;
+    int32_t packed_weights; /* 0: matrices are row-major [out][in]; 1: every matrix (the seven
+                             * of each layer and w_lm) was re-tiled by cats_pack_matrix        */
 } cats_model_desc;
 
 /* One decoder layer, bf16.  wq/wk/wv/wo: [hidden][hidden]; w_gate/w_up:
- * [ffn][hidden]; w_down: [hidden][ffn]; g_attn/g_ffn: RMSNorm gains [hidden]. */
+ * [ffn][hidden]; w_down: [hidden][ffn]; g_attn/g_ffn: RMSNorm gains [hidden].
+ * With packed_weights the seven matrices are cats_pack_matrix outputs instead. */
 typedef struct {
     const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down, *g_attn, *g_ffn;
 } cats_layer_weights;
@@ -98,6 +101,18 @@ typedef struct {
  * current device).  HOST pointers. */
 int cats_create(const cats_model_desc *desc, cats_ctx **out);
 int cats_destroy(cats_ctx *ctx);
+
+/* One-time re-tiling of a weight matrix into the order in which the weight-streaming
+ * kernel consumes it, so that every wave load is one contiguous kilobyte (the layer-weight
+ * stream of the "Target verification pass" then reads HBM purely sequentially).
+ * Layout: rows are padded to a multiple of 32 and columns to a multiple of 128 with zeros;
+ * the 1 KB fragment of row block rb (32 rows), column chunk c (128 columns) and step j
+ * (16 columns, j < 8) starts at byte ((rb * ceil(cols/128) + c) * 8 + j) * 1024 and holds,
+ * for lane l < 64, the 8 values W[32 rb + l % 32][128 c + 16 j + 8 (l / 32) .. +7].
+ * src: bf16 [rows][cols] row-major (DEVICE), cols % 16 == 0; dst: DEVICE buffer of
+ * cats_packed_matrix_bytes(rows, cols) bytes, must not overlap src. */
+size_t cats_packed_matrix_bytes(int32_t rows, int32_t cols);
+int cats_pack_matrix(const void *src, void *dst, int32_t rows, int32_t cols, void *stream);
 
 /* Validate a tree and upload it (tree ingest; the ancestor sets that form the
  * tree attention mask of Fig. 4 are derived from parent[] on the device).
@@ -150,8 +165,8 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
 /* Offload regime (Sec. 3.2: the target layers are "streamed ... chunk by chunk" while the
  * previous chunk computes; Fig. 4 left): the same verify step with the layer weights held
  * in pinned HOST memory.  host_layers: HOST array indexed by layer whose nine pointers are
- * pinned HOST addresses.  staging[0..1]: two DEVICE buffers of cats_layer_weight_bytes()
- * each; layer l is copied into staging[l & 1] on the context's own copy stream while layer
+ * pinned HOST addresses (packed matrices if the context was created with packed_weights).
+ * staging[0..1]: two DEVICE buffers of cats_layer_weight_bytes() each; layer l is copied into staging[l & 1] on the context's own copy stream while layer
  * l-1 computes on `stream` (events order the two streams; the copy of layer l+2 waits until
  * layer l has been consumed).  Everything else is as in cats_verify_tree (embed, g_final and
  * w_lm are DEVICE pointers).  The call returns after enqueueing unless out_host is given. */

@@ -16,7 +16,8 @@ __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWe
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
            "cats_accept_and_compact", "cats_verify_tree", "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
-           "cats_verify_tree_streamed", "cats_layer_weight_bytes", "layer_weights_struct", "kv_array",
+           "cats_verify_tree_streamed", "cats_layer_weight_bytes", "cats_packed_matrix_bytes",
+           "cats_pack_matrix", "pack_layer", "MATRIX_FIELDS", "layer_weights_struct", "kv_array",
            "layer_array", "kv_from_rows", "kv_to_rows", "accept_result_tensor",
            "accept_result_from_tensor", "CATS_OK", "CATS_EINVAL", "CATS_ECAPACITY", "CATS_ESTATE",
            "CATS_EHIP"]
@@ -39,7 +40,7 @@ class ModelDesc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
                 ("max_ctx", C.c_int32), ("max_tree", C.c_int32),
-                ("rms_eps", C.c_float), ("rope_base", C.c_float)]
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("packed_weights", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -83,6 +84,7 @@ _SIGNATURES = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_void_p, C.c_void_p],
+    "cats_pack_matrix": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -97,7 +99,7 @@ def library_path() -> Path:
 def exported_symbols():
     """Names every build must export (those declared in include/cats.h)."""
     return sorted(list(_SIGNATURES) + ["cats_gemm_kernel_name", "cats_strerror",
-                                       "cats_layer_weight_bytes"])
+                                       "cats_layer_weight_bytes", "cats_packed_matrix_bytes"])
 
 
 def library():
@@ -115,6 +117,8 @@ def library():
             fn.restype = C.c_int
         lib.cats_strerror.argtypes = [C.c_int]
         lib.cats_strerror.restype = C.c_char_p
+        lib.cats_packed_matrix_bytes.argtypes = [C.c_int32, C.c_int32]
+        lib.cats_packed_matrix_bytes.restype = C.c_size_t
         lib.cats_layer_weight_bytes.argtypes = [C.c_void_p]
         lib.cats_layer_weight_bytes.restype = C.c_size_t
         lib.cats_gemm_kernel_name.argtypes = []
@@ -205,6 +209,27 @@ def cats_verify_tree(ctx, layers_arr, layer_begin: int, layer_end: int, embed, h
         _dp(w_lm), kv_arr, int(ctx_len), _dp(hidden_out), _dp(logits_out), _dp(argmax_out),
         _dp(margin_out), _dp(out_dev), None if out_host is None else C.byref(out_host),
         _stream(stream)))
+
+
+def cats_packed_matrix_bytes(rows: int, cols: int) -> int:
+    return int(library().cats_packed_matrix_bytes(int(rows), int(cols)))
+
+
+def cats_pack_matrix(src, stream=None):
+    """Packed copy of a row-major bf16 [rows][cols] device tensor (new device tensor, bf16)."""
+    import torch
+    rows, cols = src.shape
+    dst = torch.empty(cats_packed_matrix_bytes(rows, cols) // 2, dtype=torch.bfloat16, device=src.device)
+    _check(library().cats_pack_matrix(_dp(src), _dp(dst), int(rows), int(cols), _stream(stream)))
+    return dst
+
+
+MATRIX_FIELDS = ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")
+
+
+def pack_layer(tensors: dict) -> dict:
+    """A layer dict with its seven matrices packed (gains unchanged)."""
+    return {k: (cats_pack_matrix(v) if k in MATRIX_FIELDS else v) for k, v in tensors.items()}
 
 
 def cats_layer_weight_bytes(desc: ModelDesc) -> int:

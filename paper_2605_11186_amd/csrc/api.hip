@@ -20,7 +20,8 @@ struct cats_ctx {
     // scratch
     float* x;        // [max_tree][H] residual stream
     // activations that feed a GEMM or the attention products: high and low bf16 parts
-    bf16_t *xn, *xn_lo;      // [max_tree][H] normalised rows
+    bf16_t *xn, *xn_lo;      // [max_tree][H] rows times gain (norm factor applied downstream)
+    float* ss;               // [max_tree][SS_STRIDE] sums of squares per column block
     bf16_t *q, *q_lo;        // [max_tree][H] rotated queries
     bf16_t *attn, *attn_lo;  // [max_tree][H] attention output
     bf16_t *hact, *hact_lo;  // [max_tree][F] SwiGLU output
@@ -79,6 +80,10 @@ int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
 
 hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 
+NormScale norm_scale(const cats_ctx* c) {
+    return NormScale{c->ss, (c->d.hidden + SS_COLS - 1) / SS_COLS, c->d.hidden, c->d.rms_eps};
+}
+
 int check_ctx_len(const cats_ctx* c, int32_t ctx_len) {
     if (!c) return CATS_EINVAL;
     if (c->T < 1) return CATS_ESTATE;
@@ -92,19 +97,27 @@ bool layer_ok(const cats_layer_weights* w) {
            w->g_ffn;
 }
 
-GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const void* w0, const void* w1, const void* w2,
-                      int seg_rows, int N, int K, hipStream_t st) {
+int seg_pad_of(const cats_ctx* c, int seg_rows) {
+    return c->d.packed_weights ? (seg_rows + PACK_ROWS - 1) / PACK_ROWS * PACK_ROWS : seg_rows;
+}
+
+// One weight-streaming product over n_seg row segments of seg_rows rows each.
+GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const void* w0, const void* w1,
+                      const void* w2, int n_seg, int seg_rows, int K, hipStream_t st) {
     GemmArgs g;
-    g.plan = make_gemm_plan(N, K, target_wgs());
     g.x = x;
     g.x_lo = x_lo;
     g.w[0] = static_cast<const bf16_t*>(w0);
     g.w[1] = static_cast<const bf16_t*>(w1 ? w1 : w0);
     g.w[2] = static_cast<const bf16_t*>(w2 ? w2 : w0);
+    g.n_seg = n_seg;
     g.seg_rows = seg_rows;
-    g.N = N;
+    g.seg_pad = seg_pad_of(c, seg_rows);
+    g.packed = c->d.packed_weights;
+    g.N = n_seg * g.seg_pad;
     g.K = K;
     g.T = c->T;
+    g.plan = make_gemm_plan(g.N, K, target_wgs());
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
@@ -148,10 +161,11 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
                    int ctx_len, const void* next_gain, hipStream_t st) {
     const int H = c->d.hidden, F = c->d.ffn, T = c->T;
     // attention block
-    GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, H, 3 * H, H, st);
+    GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, 3, H, H, st);
     QkvRopeArgs qa;
     qa.part = c->part;
     qa.plan = plan;
+    qa.ns = norm_scale(c);
     qa.cs = c->rope_cs;
     qa.q = c->q;
     qa.q_lo = c->q_lo;
@@ -165,7 +179,7 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.ctx_len = ctx_len;
     launch_qkv_rope(qa, st);
     enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, st);
-    plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, H, H, H, st);
+    plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
     rn.x_in = nullptr;
@@ -176,21 +190,24 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     rn.gain = static_cast<const bf16_t*>(w->g_ffn);
     rn.xn = c->xn;
     rn.xn_lo = c->xn_lo;
+    rn.ss = c->ss;
     rn.T = T;
     rn.H = H;
     rn.eps = c->d.rms_eps;
     launch_residual_norm(rn, st);
     // feed-forward block
-    plan = enqueue_gemm(c, c->xn, c->xn_lo, w->w_gate, w->w_up, nullptr, F, 2 * F, H, st);
+    plan = enqueue_gemm(c, c->xn, c->xn_lo, w->w_gate, w->w_up, nullptr, 2, F, H, st);
     SwigluArgs sa;
     sa.part = c->part;
     sa.plan = plan;
+    sa.ns = norm_scale(c);
     sa.h = c->hact;
     sa.h_lo = c->hact_lo;
     sa.T = T;
     sa.F = F;
+    sa.f_pad = seg_pad_of(c, F);
     launch_swiglu(sa, st);
-    plan = enqueue_gemm(c, c->hact, c->hact_lo, w->w_down, nullptr, nullptr, H, H, F, st);
+    plan = enqueue_gemm(c, c->hact, c->hact_lo, w->w_down, nullptr, nullptr, 1, H, F, st);
     rn.plan = plan;
     rn.gain = static_cast<const bf16_t*>(next_gain);
     launch_residual_norm(rn, st);
@@ -209,12 +226,14 @@ void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
 
 void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
                      float* margin_out, hipStream_t st) {
-    const GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, c->d.vocab, c->d.vocab, c->d.hidden, st);
+    const GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
     ArgmaxArgs am;
     am.part = c->part;
     am.plan = plan;
+    am.ns = norm_scale(c);
     am.T = c->T;
     am.V = c->d.vocab;
+    am.ld = seg_pad_of(c, c->d.vocab);
     am.logits = logits_out;
     am.amax = argmax_out;
     am.margin = margin_out;
@@ -265,7 +284,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
         d.hidden > 8192 || d.n_heads < 1 || (d.head_dim != 64 && d.head_dim != 128) ||
         d.n_heads * d.head_dim != d.hidden || d.ffn < 16 || d.ffn % 16 != 0 || d.vocab < 2 ||
         d.max_ctx < 64 || d.max_ctx % 64 != 0 || d.max_tree < 1 || d.max_tree > CATS_MAX_TREE ||
-        !(d.rms_eps > 0.f) || !(d.rope_base > 1.f))
+        !(d.rms_eps > 0.f) || !(d.rope_base > 1.f) || (d.packed_weights != 0 && d.packed_weights != 1))
         return CATS_EINVAL;
     cats_ctx* c = new (std::nothrow) cats_ctx();
     if (!c) return CATS_EHIP;
@@ -283,8 +302,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t Tm = d.max_tree, H = d.hidden, F = d.ffn;
     // split-K partials: the largest splits*N over the five GEMM shapes
     size_t part_cols = 0;
-    const int shapes[5][2] = {{3 * d.hidden, d.hidden}, {d.hidden, d.hidden}, {2 * d.ffn, d.hidden},
-                              {d.hidden, d.ffn}, {d.vocab, d.hidden}};
+    const auto pad32 = [&](int n) { return d.packed_weights ? (n + 31) / 32 * 32 : n; };
+    const int shapes[5][2] = {{3 * d.hidden, d.hidden}, {d.hidden, d.hidden}, {2 * pad32(d.ffn), d.hidden},
+                              {d.hidden, d.ffn}, {pad32(d.vocab), d.hidden}};
     for (auto& s : shapes)
         part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
                                             make_gemm_plan(s[0], s[1], target_wgs()))) * s[0]);
@@ -302,6 +322,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_attn = take(Tm * H * 2), o_h = take(Tm * F * 2);
     const size_t o_xn_lo = take(Tm * H * 2), o_q_lo = take(Tm * H * 2), o_attn_lo = take(Tm * H * 2);
     const size_t o_h_lo = take(Tm * F * 2);
+    const size_t o_ss = take(Tm * SS_STRIDE * 4);
     const size_t o_part = take(c->part_elems * 4);
     const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
@@ -331,6 +352,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->q_lo = reinterpret_cast<bf16_t*>(b + o_q_lo);
     c->attn_lo = reinterpret_cast<bf16_t*>(b + o_attn_lo);
     c->hact_lo = reinterpret_cast<bf16_t*>(b + o_h_lo);
+    c->ss = reinterpret_cast<float*>(b + o_ss);
     c->part = reinterpret_cast<float*>(b + o_part);
     c->rope_cs = reinterpret_cast<float2*>(b + o_cs);
     c->attn_po = reinterpret_cast<float*>(b + o_po);
@@ -397,6 +419,7 @@ int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden,
     rn.gain = static_cast<const bf16_t*>(w->g_attn);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
+    rn.ss = ctx->ss;
     rn.T = ctx->T;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
@@ -446,6 +469,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final,
     rn.gain = static_cast<const bf16_t*>(g_final);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
+    rn.ss = ctx->ss;
     rn.T = ctx->T;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
@@ -483,6 +507,7 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : g_final);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
+    rn.ss = ctx->ss;
     rn.T = T;
     rn.H = H;
     rn.eps = ctx->d.rms_eps;
@@ -523,10 +548,34 @@ int cats_profile_gemm_read(cats_ctx* ctx, float* total_ms, int32_t* launches) {
     return CATS_OK;
 }
 
+// bf16 elements of the nine arrays of one layer, in staging order
+static void layer_array_elems(const cats_model_desc& d, size_t out[9]) {
+    const int H = d.hidden, F = d.ffn;
+    const int shp[7][2] = {{H, H}, {H, H}, {H, H}, {H, H}, {F, H}, {F, H}, {H, F}};
+    for (int i = 0; i < 7; ++i)
+        out[i] = d.packed_weights ? packed_matrix_elems(shp[i][0], shp[i][1])
+                                  : static_cast<size_t>(shp[i][0]) * shp[i][1];
+    out[7] = out[8] = H;
+}
+
 size_t cats_layer_weight_bytes(const cats_model_desc* desc) {
     if (!desc) return 0;
-    const size_t H = desc->hidden, F = desc->ffn;
-    return (4 * H * H + 3 * H * F + 2 * H) * sizeof(bf16_t);
+    size_t e[9], tot = 0;
+    layer_array_elems(*desc, e);
+    for (size_t v : e) tot += v;
+    return tot * sizeof(bf16_t);
+}
+
+size_t cats_packed_matrix_bytes(int32_t rows, int32_t cols) {
+    if (rows < 1 || cols < 1) return 0;
+    return packed_matrix_elems(rows, cols) * sizeof(bf16_t);
+}
+
+int cats_pack_matrix(const void* src, void* dst, int32_t rows, int32_t cols, void* stream) {
+    if (!src || !dst || rows < 1 || cols < 16 || cols % 16 != 0) return CATS_EINVAL;
+    launch_pack_matrix(static_cast<const bf16_t*>(src), static_cast<bf16_t*>(dst), rows, cols, as_stream(stream));
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
 }
 
 int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_layers, int32_t layer_begin,
@@ -552,10 +601,11 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
         }
     }
     hipStream_t st = as_stream(stream), cs = ctx->copy_stream;
-    const size_t H = ctx->d.hidden, F = ctx->d.ffn;
+    const size_t H = ctx->d.hidden;
     const int T = ctx->T;
     // layout of one staged layer: wq | wk | wv | wo | w_gate | w_up | w_down | g_attn | g_ffn
-    const size_t sizes[9] = {H * H, H * H, H * H, H * H, F * H, F * H, H * F, H, H};
+    size_t sizes[9];
+    layer_array_elems(ctx->d, sizes);
     auto staged = [&](int b) {
         cats_layer_weights w;
         const void** fields[9] = {&w.wq, &w.wk, &w.wv, &w.wo, &w.w_gate, &w.w_up, &w.w_down, &w.g_attn, &w.g_ffn};
@@ -598,6 +648,7 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
     rn.gain = nullptr;  // input rows only; each layer's first norm is launched once its gains have arrived
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
+    rn.ss = ctx->ss;
     rn.T = T;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;

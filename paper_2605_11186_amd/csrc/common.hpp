@@ -61,15 +61,23 @@ __host__ __device__ inline int plan_pieces(const GemmPlan& p, int tile) {
 // mantissa bits: bf16 weights times (hi + lo) on the bf16 MFMA keeps the products close to
 // fp32 accuracy, which the exact-acceptance requirement needs (a single bf16 rounding of
 // every GEMM input moves 7B-scale logits by several 1e-2).
+// Output column v of the product belongs to weight segment v / seg_pad, row v % seg_pad of
+// it; seg_pad is seg_rows for row-major weights and seg_rows rounded up to 32 for packed ones
+// (columns whose row index is >= seg_rows do not exist and are never written).
 struct GemmArgs {
     const bf16_t* x;     // [T][K] high parts
     const bf16_t* x_lo;  // [T][K] low parts
     const bf16_t* w[3];
-    int seg_rows;
-    int N, K, T;
+    int n_seg, seg_rows, seg_pad;
+    int packed;  // weights are cats_pack_matrix outputs
+    int N, K, T;  // N = n_seg * seg_pad
     GemmPlan plan;
     float* part;  // [pieces][T][N]
 };
+constexpr int PACK_ROWS = 32;   // rows per packed row block
+constexpr int PACK_FRAG = 512;  // bf16 elements per packed 1 KB fragment
+void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t st);
+size_t packed_matrix_elems(int rows, int cols);
 #ifndef CATS_GEMM_BN
 #define CATS_GEMM_BN 256
 #endif
@@ -96,6 +104,29 @@ __device__ __forceinline__ float sum_pieces(const float* part, const GemmPlan& p
 }
 
 // ---------------------------------------------------------------- row kernels
+// RMSNorm is applied in two halves so that no kernel needs a whole row at once: the kernel
+// that updates the residual stream writes x*gain (not yet scaled) as the next GEMM's input
+// and, per block of 256 columns, the sum of squares of x; the kernel that consumes that
+// GEMM's output multiplies by 1/sqrt(mean(x^2)+eps), which commutes with the product.
+constexpr int SS_COLS = 256;   // columns per sum-of-squares block
+constexpr int SS_STRIDE = 32;  // blocks per row kept in scratch (hidden <= 8192)
+struct NormScale {
+    const float* ss;  // [T][SS_STRIDE]
+    int n_ss;         // blocks in use
+    int H;
+    float eps;
+};
+// Entries past n_ss are never written and stay zero, so the whole row of SS_STRIDE floats is
+// added up with eight independent 16-byte loads (fixed order: deterministic).
+__device__ __forceinline__ float row_scale(const NormScale& ns, int t) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(ns.ss + t * SS_STRIDE);
+    f32x4 acc = p[0];
+#pragma unroll
+    for (int b = 1; b < SS_STRIDE / 4; ++b) acc += p[b];
+    const float tot = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    return 1.0f / sqrtf(tot / static_cast<float>(ns.H) + ns.eps);
+}
+
 struct ResidualNormArgs {
     float* x;               // [T][H] residual stream, in/out
     const float* x_in;      // optional [T][H]: start from this instead of x
@@ -103,9 +134,10 @@ struct ResidualNormArgs {
     const int32_t* token;   // device [T]
     const float* part;      // optional [pieces][T][H] partial sums to add
     GemmPlan plan;
-    const bf16_t* gain;     // optional [H]: if given, xn = rmsnorm(x) * gain
-    bf16_t* xn;             // [T][H] high parts of the normalised row
+    const bf16_t* gain;     // optional [H]: if given, xn = x * gain (unscaled) and ss are written
+    bf16_t* xn;             // [T][H] high parts of x * gain
     bf16_t* xn_lo;          // [T][H] low parts
+    float* ss;              // [T][SS_STRIDE] sums of squares of x per block of SS_COLS columns
     int T, H;
     float eps;
 };
@@ -120,8 +152,9 @@ struct RopeTableArgs {
 void launch_rope_table(const RopeTableArgs& a, hipStream_t st);
 
 struct QkvRopeArgs {
-    const float* part;  // [pieces][T][3H]: q | k | v
+    const float* part;  // [pieces][T][3H]: q | k | v, still to be scaled by the row's norm factor
     GemmPlan plan;
+    NormScale ns;
     const float2* cs;   // [T][d/2]
     bf16_t* q;          // [T][H] high parts of the rotated queries
     bf16_t* q_lo;       // [T][H] low parts
@@ -132,18 +165,22 @@ struct QkvRopeArgs {
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
 
 struct SwigluArgs {
-    const float* part;  // [pieces][T][2F]: gate | up
+    const float* part;  // [pieces][T][2F]: gate | up, still to be scaled by the row's norm factor
     GemmPlan plan;
+    NormScale ns;
     bf16_t* h;          // [T][F] high parts
     bf16_t* h_lo;       // [T][F] low parts
     int T, F;
+    int f_pad;          // column offset of the up half inside a row of part (row length 2*f_pad)
 };
 void launch_swiglu(const SwigluArgs& a, hipStream_t st);
 
 struct ArgmaxArgs {
-    const float* part;  // [pieces][T][V]
+    const float* part;  // [pieces][T][V], still to be scaled by the row's norm factor
     GemmPlan plan;
+    NormScale ns;
     int T, V;
+    int ld;             // row length of part (V rounded up for packed weights)
     float* logits;      // optional [T][V]
     int32_t* amax;      // [T]
     float* margin;      // optional [T]

@@ -34,7 +34,8 @@ __device__ __forceinline__ void lds_barrier() {
 // lane are D[8*(r/4) + 4*(l/32) + r%4][l%32].
 //
 // TB: 32-row blocks of X (T <= 32*TB).  NW: waves per workgroup.  ST: ring depth.
-template <int TB, int NW, int ST>
+// PACKED: weights come in the packed fragment order (contiguous 1 KB per wave load).
+template <int TB, int NW, int ST, bool PACKED>
 __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
     constexpr int THREADS = 64 * NW;
     constexpr int BN = 32 * NW;
@@ -73,6 +74,10 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
         x_off[p] = static_cast<size_t>(min(r, a.T - 1)) * a.K;
     }
     const int k_last_x = a.K - 8, k_last_w = a.K - 16;
+    const int rb_per_seg = a.seg_pad / PACK_ROWS, n_rb_total = a.n_seg * rb_per_seg;  // packed only
+    (void)rb_per_seg;
+    (void)n_rb_total;
+    (void)k_last_w;
 
     // item (local index i) -> tile and first k of its chunk
 #define CATS_ITEM(i, tile_, k0_)                  \
@@ -92,15 +97,27 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
         }                                                                                           \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
+    // Weight address of this lane for item i.  Row-major: row v of the product, 8 k-values
+    // from column 16 j + 8 g of the chunk (clamped inside the row).  Packed: the wave's 32-row
+    // block is one contiguous run of 1 KB fragments, 8 per chunk, lane l owning bytes 16 l.
 #define CATS_LOAD_W(slot, i)                                                                        \
     {                                                                                               \
         CATS_ITEM(i, lt_, lk_)                                                                      \
-        const int ln_ = min(lt_ * BN + wave * 32 + col, a.N - 1);                                   \
-        const int lseg_ = ln_ / a.seg_rows;                                                         \
-        const bf16_t* lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                \
-                            static_cast<size_t>(ln_ - lseg_ * a.seg_rows) * a.K + 8 * g;            \
+        const bf16_t* lw_;                                                                          \
+        if (PACKED) {                                                                               \
+            const int lrb_ = min((lt_ * BN + wave * 32) / PACK_ROWS, n_rb_total - 1);               \
+            const int lseg_ = lrb_ / rb_per_seg;                                                    \
+            lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                          \
+                  (static_cast<size_t>(lrb_ - lseg_ * rb_per_seg) * C + lk_ / GEMM_KC) * (8 * PACK_FRAG) + lane * 8; \
+        } else {                                                                                    \
+            const int lv_ = min(lt_ * BN + wave * 32 + col, a.N - 1);                               \
+            const int lseg_ = lv_ / a.seg_pad;                                                      \
+            lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                          \
+                  static_cast<size_t>(min(lv_ - lseg_ * a.seg_pad, a.seg_rows - 1)) * a.K + 8 * g;  \
+        }                                                                                           \
         _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
-            wst[slot][j] = *reinterpret_cast<const u32x4*>(lw_ + min(lk_ + 16 * j, k_last_w));      \
+            wst[slot][j] = *reinterpret_cast<const u32x4*>(                                         \
+                PACKED ? lw_ + j * PACK_FRAG : lw_ + min(lk_ + 16 * j, k_last_w));                  \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
@@ -138,7 +155,7 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
         }                                                                                           \
         if (k0 + GEMM_KC >= a.K || (i) == n_items - 1) {                                            \
             const int n = tile * BN + wave * 32 + col;                                              \
-            if (n < a.N) {                                                                          \
+            if (n < a.N && n % a.seg_pad < a.seg_rows) {                                            \
                 const int piece = wg - plan_first_wg(a.plan, tile);                                 \
                 float* out = a.part + static_cast<size_t>(piece) * a.T * a.N + n;                   \
                 _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                   \
@@ -195,7 +212,36 @@ __global__ __launch_bounds__(64 * NW) void cats_gemm_skinny_bf16(GemmArgs a) {
 #undef CATS_ITEM
 }
 
+// One thread per 16 bytes of the packed matrix: fragment f = (rb * C + c) * 8 + j, lane l.
+__global__ void cats_pack_matrix_kernel(const bf16_t* src, bf16_t* dst, int rows, int cols, int C, size_t n_vec) {
+    const size_t idx = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (idx >= n_vec) return;
+    const int l = static_cast<int>(idx & 63);
+    const size_t f = idx >> 6;
+    const int j = static_cast<int>(f & 7);
+    const size_t rc = f >> 3;
+    const int c = static_cast<int>(rc % C);
+    const int rb = static_cast<int>(rc / C);
+    const int row = rb * PACK_ROWS + (l & 31);
+    const int k = c * GEMM_KC + 16 * j + 8 * (l >> 5);
+    u32x4 v = u32x4{0u, 0u, 0u, 0u};
+    if (row < rows && k < cols) v = *reinterpret_cast<const u32x4*>(src + static_cast<size_t>(row) * cols + k);
+    reinterpret_cast<u32x4*>(dst)[idx] = v;
+}
+
 }  // namespace
+
+size_t packed_matrix_elems(int rows, int cols) {
+    const size_t rb = (rows + PACK_ROWS - 1) / PACK_ROWS, C = (cols + GEMM_KC - 1) / GEMM_KC;
+    return rb * C * 8 * PACK_FRAG;
+}
+
+void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t st) {
+    const size_t n_vec = packed_matrix_elems(rows, cols) / 8;
+    const int C = (cols + GEMM_KC - 1) / GEMM_KC;
+    hipLaunchKernelGGL(cats_pack_matrix_kernel, dim3(static_cast<unsigned>((n_vec + 255) / 256)), dim3(256), 0, st,
+                       src, dst, rows, cols, C, n_vec);
+}
 
 GemmPlan make_gemm_plan(int N, int K, int target_wgs) {
     GemmPlan p;
@@ -223,8 +269,13 @@ void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEven
     constexpr int NW = GEMM_BN / 32;
     const dim3 grid(a.plan.n_wgs), block(64 * NW);
     const int tb = (a.T + 31) / 32;
-#define CATS_LAUNCH(TBV, STV)                                                                         \
-    hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV>), grid, block, 0, st, ev_start, ev_stop, 0, a)
+#define CATS_LAUNCH(TBV, STV)                                                                          \
+    if (a.packed)                                                                                      \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV, true>), grid, block, 0, st, ev_start, \
+                              ev_stop, 0, a);                                                          \
+    else                                                                                               \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV, false>), grid, block, 0, st, ev_start, \
+                              ev_stop, 0, a)
     switch (tb) {
         case 1: CATS_LAUNCH(1, GEMM_ST); break;
         case 2: CATS_LAUNCH(2, GEMM_ST); break;

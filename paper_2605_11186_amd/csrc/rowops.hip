@@ -13,66 +13,47 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// x[t] <- (x_in[t] | embed[token[t]] | x[t]) + sum_s part[s][t];  xn[t] = rmsnorm(x[t]) * gain
-// One workgroup of 1024 threads per row; a thread owns float4 groups j = 4*tid + 4096*i, so
-// all of its partial-sum loads are independent 16-byte loads that can be in flight together.
-constexpr int RN_THREADS = 1024;
-constexpr int RN_MAX_GROUPS = 2;  // hidden <= 8192
-__global__ __launch_bounds__(RN_THREADS) void cats_residual_rmsnorm(ResidualNormArgs a) {
-    __shared__ float red[RN_THREADS / 64];
-    const int t = blockIdx.x;
-    const int tid = threadIdx.x;
-    f32x4 v[RN_MAX_GROUPS];
+// x[t] <- (x_in[t] | embed[token[t]] | x[t]) + sum of the GEMM pieces;  xn[t] = x[t] * gain as
+// high + low bf16 parts;  ss[t][block] = sum of x^2 over the block's columns.  One wave per
+// (row, block of 256 columns): nothing here needs a whole row, so the launch has T * H/256
+// independent waves.
+__global__ __launch_bounds__(64) void cats_residual_rmsnorm(ResidualNormArgs a) {
+    const int t = blockIdx.x, blk = blockIdx.y;
+    const int j = blk * SS_COLS + 4 * threadIdx.x;
     float ss = 0.f;
-    const size_t row = static_cast<size_t>(t) * a.H;
-    const bf16_t* erow = a.embed ? a.embed + static_cast<size_t>(a.token[t]) * a.H : nullptr;
-    const bool write_x = erow || a.x_in || a.part;
-#pragma unroll
-    for (int i = 0; i < RN_MAX_GROUPS; ++i) {
-        const int j = 4 * tid + 4 * RN_THREADS * i;
-        if (j < a.H) {
-            f32x4 val;
-            if (erow) {
-                const uint2 e = *reinterpret_cast<const uint2*>(erow + j);
-                val = f32x4{__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xFFFF0000u),
-                            __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xFFFF0000u)};
-            } else {
-                val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
-            }
-            if (a.part) {
-                const float* pp = a.part + row + j;
-                const size_t stride = static_cast<size_t>(a.T) * a.H;
-                const int pieces = plan_pieces(a.plan, j / a.plan.bn);
-#pragma unroll 8
-                for (int s = 0; s < pieces; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
-            }
-            v[i] = val;
-            ss += val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
-            if (write_x) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
+    if (j < a.H) {
+        const size_t row = static_cast<size_t>(t) * a.H;
+        f32x4 val;
+        if (a.embed) {
+            const uint2 e = *reinterpret_cast<const uint2*>(a.embed + static_cast<size_t>(a.token[t]) * a.H + j);
+            val = f32x4{__uint_as_float(e.x << 16), __uint_as_float(e.x & 0xFFFF0000u),
+                        __uint_as_float(e.y << 16), __uint_as_float(e.y & 0xFFFF0000u)};
+        } else {
+            val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
         }
-    }
-    if (!a.gain) return;
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    float tot = 0.f;
-#pragma unroll
-    for (int w = 0; w < RN_THREADS / 64; ++w) tot += red[w];
-    const float scale = 1.0f / sqrtf(tot / static_cast<float>(a.H) + a.eps);
-#pragma unroll
-    for (int i = 0; i < RN_MAX_GROUPS; ++i) {
-        const int j = 4 * tid + 4 * RN_THREADS * i;
-        if (j < a.H) {
+        if (a.part) {
+            const float* pp = a.part + row + j;
+            const size_t stride = static_cast<size_t>(a.T) * a.H;
+            const int pieces = plan_pieces(a.plan, j / a.plan.bn);
+#pragma unroll 8
+            for (int s = 0; s < pieces; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
+        }
+        ss = val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
+        if (a.embed || a.x_in || a.part) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
+        if (a.gain) {
             const uint2 gbits = *reinterpret_cast<const uint2*>(a.gain + j);
             uint2 hi, lo;
-            split_bf2(v[i][0] * scale * __uint_as_float(gbits.x << 16),
-                      v[i][1] * scale * __uint_as_float(gbits.x & 0xFFFF0000u), hi.x, lo.x);
-            split_bf2(v[i][2] * scale * __uint_as_float(gbits.y << 16),
-                      v[i][3] * scale * __uint_as_float(gbits.y & 0xFFFF0000u), hi.y, lo.y);
+            split_bf2(val[0] * __uint_as_float(gbits.x << 16), val[1] * __uint_as_float(gbits.x & 0xFFFF0000u),
+                      hi.x, lo.x);
+            split_bf2(val[2] * __uint_as_float(gbits.y << 16), val[3] * __uint_as_float(gbits.y & 0xFFFF0000u),
+                      hi.y, lo.y);
             *reinterpret_cast<uint2*>(a.xn + row + j) = hi;
             *reinterpret_cast<uint2*>(a.xn_lo + row + j) = lo;
         }
     }
+    if (!a.gain) return;
+    ss = wave_sum(ss);
+    if (threadIdx.x == 0) a.ss[t * SS_STRIDE + blk] = ss;
 }
 
 // cos/sin of pos * base^(-2j/d) for pos = ctx_len + depth[t]; computed in double so
@@ -89,10 +70,12 @@ __global__ void cats_rope_table(RopeTableArgs a) {
 
 // Adds up q|k|v partials, rotates q and k (pairs j, j+d/2), writes q (high and low bf16
 // parts), appends the key row and the (transposed) value column of every node at cache row
-// ctx_len + t.  grid (T, nh), block d/2.
-__global__ void cats_qkv_rope_append(QkvRopeArgs a) {
-    const int t = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+// ctx_len + t.  grid (T, groups of heads), block 256: one thread per (head, pair).
+__global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
     const int half = a.d / 2;
+    const int heads_per_block = 256 / half;
+    const int t = blockIdx.x, h = blockIdx.y * heads_per_block + threadIdx.x / half, j = threadIdx.x % half;
+    if (h >= a.nh) return;
     const int N = 3 * a.H;
     float v6[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     const int c0 = h * a.d + j;
@@ -109,6 +92,9 @@ __global__ void cats_qkv_rope_append(QkvRopeArgs a) {
             v6[2 * m + 1] += p[s * stride + half];
         }
     }
+    const float rs = row_scale(a.ns, t);
+#pragma unroll
+    for (int m = 0; m < 6; ++m) v6[m] *= rs;
     const float2 cs = a.cs[t * half + j];
     const float q0 = v6[0] * cs.x - v6[1] * cs.y, q1 = v6[0] * cs.y + v6[1] * cs.x;
     const float k0 = v6[2] * cs.x - v6[3] * cs.y, k1 = v6[2] * cs.y + v6[3] * cs.x;
@@ -133,7 +119,7 @@ __global__ void cats_swiglu(SwigluArgs a) {
     const int half_f = a.F / 2;
     if (idx >= a.T * half_f) return;
     const int t = idx / half_f, n = 2 * (idx - t * half_f);
-    const int N = 2 * a.F;
+    const int N = 2 * a.f_pad;
     float gt[2] = {0.f, 0.f}, up[2] = {0.f, 0.f};
     const size_t stride = static_cast<size_t>(a.T) * N;
     {
@@ -146,13 +132,19 @@ __global__ void cats_swiglu(SwigluArgs a) {
         }
     }
     {
-        const int pieces = plan_pieces(a.plan, (a.F + n) / a.plan.bn);
-        const float* p = a.part + static_cast<size_t>(t) * N + a.F + n;
+        const int pieces = plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn);
+        const float* p = a.part + static_cast<size_t>(t) * N + a.f_pad + n;
         for (int s = 0; s < pieces; ++s) {
             const float2 v = *reinterpret_cast<const float2*>(p + s * stride);
             up[0] += v.x;
             up[1] += v.y;
         }
+    }
+    const float rs = row_scale(a.ns, t);
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        gt[m] *= rs;
+        up[m] *= rs;
     }
     uint32_t hi, lo;
     split_bf2(gt[0] / (1.0f + __expf(-gt[0])) * up[0], gt[1] / (1.0f + __expf(-gt[1])) * up[1], hi, lo);
@@ -170,8 +162,9 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
     const int t = blockIdx.x, tid = threadIdx.x;
     float best = -INFINITY, second = -INFINITY;
     int bidx = 0x7fffffff;
+    const float rs = row_scale(a.ns, t);
     for (int v = tid; v < a.V; v += AM_THREADS) {
-        const float val = sum_pieces(a.part, a.plan, a.T, a.V, t, v);
+        const float val = rs * sum_pieces(a.part, a.plan, a.T, a.ld, t, v);
         if (a.logits) a.logits[static_cast<size_t>(t) * a.V + v] = val;
         if (val > best) {  // indices ascend within a thread: strict > keeps the lowest
             second = best;
@@ -212,7 +205,7 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
 }  // namespace
 
 void launch_residual_norm(const ResidualNormArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(cats_residual_rmsnorm, dim3(a.T), dim3(RN_THREADS), 0, st, a);
+    hipLaunchKernelGGL(cats_residual_rmsnorm, dim3(a.T, (a.H + SS_COLS - 1) / SS_COLS), dim3(64), 0, st, a);
 }
 
 void launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
@@ -221,7 +214,9 @@ void launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
 }
 
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T, a.nh), dim3(a.d / 2), 0, st, a);
+    const int heads_per_block = 256 / (a.d / 2);
+    hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T, (a.nh + heads_per_block - 1) / heads_per_block), dim3(256),
+                       0, st, a);
 }
 
 void launch_swiglu(const SwigluArgs& a, hipStream_t st) {

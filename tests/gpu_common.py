@@ -32,7 +32,7 @@ def bf16_to_f32_np(t: torch.Tensor) -> np.ndarray:
 class Pair:
     """One model on both sides."""
 
-    def __init__(self, dims, seed, max_ctx, max_tree, precision="f64", n_layers=None):
+    def __init__(self, dims, seed, max_ctx, max_tree, precision="f64", n_layers=None, packed=False):
         self.dims = dims
         self.max_ctx = max_ctx
         L = dims.n_layers if n_layers is None else n_layers
@@ -42,12 +42,18 @@ class Pair:
         self.embed = synth.embedding(dims, seed)
         self.oracle = Oracle(dims, self.layers + [None] * (dims.n_layers - L), self.final, self.embed,
                              precision=precision)
-        self.d_layers = [{k: to_dev_bf16(v) for k, v in w.items()} for w in self.layers]
+        self.packed = packed
+        self.d_layers = []
+        for w in self.layers:   # packed layout: re-tile on the device, drop the row-major copy
+            dw = {k: to_dev_bf16(v) for k, v in w.items()}
+            self.d_layers.append(cats.pack_layer(dw) if packed else dw)
         self.d_final = {k: to_dev_bf16(v) for k, v in self.final.items()}
+        if packed:
+            self.d_final["w_lm"] = cats.cats_pack_matrix(self.d_final["w_lm"])
         self.d_embed = to_dev_bf16(self.embed)
         self.layers_arr = cats.layer_array(self.d_layers)
         desc = cats.ModelDesc(dims.n_layers, dims.hidden, dims.n_heads, dims.head_dim, dims.ffn,
-                              dims.vocab, max_ctx, max_tree, dims.rms_eps, dims.rope_base)
+                              dims.vocab, max_ctx, max_tree, dims.rms_eps, dims.rope_base, int(packed))
         self.ctx = cats.cats_create(desc)
         self.res_dev = cats.accept_result_tensor()
 

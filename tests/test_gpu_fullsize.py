@@ -82,7 +82,7 @@ def test_7b_full_verify_step_matches_oracle():
     dims = synth.V7B
     parent, depth, _ = synth.product_tree_pruned()
     T, S = len(parent), 1024
-    pair = Pair(dims, BENCH_SEED, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32")
+    pair = Pair(dims, BENCH_SEED, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", packed=True)
     try:
         tok = synth.distinct_sibling_tokens(parent, dims.vocab, BENCH_SEED)
         deep = int(np.flatnonzero(depth == 3)[0])
@@ -95,7 +95,7 @@ def test_13b_layer_shape_three_layers():
     dims = synth.V13B
     parent, depth = synth.random_tree(64, 7, 4)
     S = 2048
-    pair = Pair(dims, 13, max_ctx=2112, max_tree=64, precision="f32", n_layers=3)
+    pair = Pair(dims, 13, max_ctx=2112, max_tree=64, precision="f32", n_layers=3, packed=True)
     try:
         tok = synth.distinct_sibling_tokens(parent, dims.vocab, 13)
         compare_with_oracle(pair, S, tok, parent, depth, 13)
@@ -109,7 +109,7 @@ def test_7b_layer_shape_tree_and_context_sweep(T, S):
     two 7B-shaped layers each."""
     dims = synth.V7B
     parent, depth = synth.random_tree(T, 8, T)
-    pair = Pair(dims, 7, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", n_layers=2)
+    pair = Pair(dims, 7, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", n_layers=2, packed=(T != 16))
     try:
         tok = synth.distinct_sibling_tokens(parent, dims.vocab, T)
         compare_with_oracle(pair, S, tok, parent, depth, S)

@@ -16,9 +16,10 @@ pytestmark = pytest.mark.gpu
 SEED = 2024
 
 
-@pytest.fixture(scope="module")
-def tiny():
-    p = Pair(synth.TINY, SEED, max_ctx=320, max_tree=128)
+@pytest.fixture(scope="module", params=[False, True], ids=["rowmajor", "packed"])
+def tiny(request):
+    """The tiny model with row-major weights and with weights re-tiled by cats_pack_matrix."""
+    p = Pair(synth.TINY, SEED, max_ctx=320, max_tree=128, packed=request.param)
     yield p
     p.close()
 
@@ -334,14 +335,16 @@ def test_error_codes_from_host_validation(tiny):
                               tiny.d_final["g_final"], tiny.d_final["w_lm"], cats.kv_array(ks, vs), 0,
                               tiny.res_dev)
     assert e.value.status == cats.CATS_EINVAL
-    desc = cats.ModelDesc(2, 256, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0)
+    desc = cats.ModelDesc(2, 256, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0, 0)
     fresh = cats.cats_create(desc)
     with pytest.raises(cats.CatsError) as e:   # no tree yet
         cats.cats_tree_attention(fresh, ks[0], cats.KVLayer(ks[0].data_ptr(), vs[0].data_ptr()), 0, ks[0])
     assert e.value.status == cats.CATS_ESTATE
     cats.cats_destroy(fresh)
     with pytest.raises(cats.CatsError):
-        cats.cats_create(cats.ModelDesc(2, 250, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0))
+        cats.cats_create(cats.ModelDesc(2, 250, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0, 0))
+    with pytest.raises(cats.CatsError):   # layout flag must be 0 or 1
+        cats.cats_create(cats.ModelDesc(2, 256, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0, 7))
 
 
 def test_streamed_weights_give_the_same_step(tiny):
@@ -355,11 +358,13 @@ def test_streamed_weights_give_the_same_step(tiny):
     kc, vc = tiny.oracle_cache_random(77, S)
     outs = []
     desc = cats.ModelDesc(d.n_layers, d.hidden, d.n_heads, d.head_dim, d.ffn, d.vocab, tiny.max_ctx, 128,
-                          d.rms_eps, d.rope_base)
+                          d.rms_eps, d.rope_base, int(tiny.packed))
     nbytes = cats.cats_layer_weight_bytes(desc)
-    assert nbytes == d.layer_weight_elems() * 2
-    host_layers = [{k: torch.from_numpy(v.view(np.int16).copy()).pin_memory() for k, v in w.items()}
-                   for w in tiny.layers]
+    if not tiny.packed:
+        assert nbytes == d.layer_weight_elems() * 2
+    # the host copies hold exactly what the device layers hold (packed or not)
+    host_layers = [{k: v.cpu().view(torch.int16).pin_memory() for k, v in w.items()} for w in tiny.d_layers]
+    assert nbytes == sum(v.numel() * 2 for v in host_layers[0].values())
     staging = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
     for streamed in (False, True, True):
         ks, vs = tiny.device_cache_from_oracle(kc, vc, S)
@@ -385,3 +390,22 @@ def test_streamed_weights_give_the_same_step(tiny):
     # and against the oracle
     o_hidden = tiny.oracle.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=tiny.L)
     assert rel_err(outs[1][0].numpy(), o_hidden) <= REL_TOL
+
+
+def test_pack_matrix_layout_is_the_documented_one():
+    """cats_pack_matrix against the layout spelled out in the header, computed in numpy."""
+    rng = np.random.default_rng(5)
+    for rows, cols in [(32, 128), (70, 272), (688, 256), (256, 688)]:
+        bits = rng.integers(0, 1 << 16, size=(rows, cols), dtype=np.uint16)
+        packed = cats.cats_pack_matrix(to_dev_bf16(bits)).view(torch.int16).cpu().numpy().view(np.uint16)
+        C = -(-cols // 128)
+        rb_n = -(-rows // 32)
+        assert packed.size * 2 == cats.cats_packed_matrix_bytes(rows, cols) == rb_n * C * 8 * 1024
+        padded = np.zeros((rb_n * 32, C * 128), np.uint16)
+        padded[:rows, :cols] = bits
+        ref = np.empty((rb_n, C, 8, 64, 8), np.uint16)
+        for l in range(64):
+            for j in range(8):
+                k0 = 16 * j + 8 * (l // 32)
+                ref[:, :, j, l, :] = padded.reshape(rb_n, 32, C, 128)[:, l % 32, :, k0:k0 + 8]
+        assert np.array_equal(packed, ref.reshape(-1))

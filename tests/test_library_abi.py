@@ -33,8 +33,8 @@ def test_status_strings_and_kernel_name():
 
 
 def test_struct_layouts_match_header_sizes():
-    # 8 int32 + 2 float; 9 pointers; 2 pointers; 1 + 17 + 17 + 1 + 1 int32
-    assert ctypes.sizeof(cats.ModelDesc) == 40
+    # 8 int32 + 2 float + 1 int32; 9 pointers; 2 pointers; 1 + 17 + 17 + 1 + 1 int32
+    assert ctypes.sizeof(cats.ModelDesc) == 44
     assert ctypes.sizeof(cats.LayerWeights) == 72
     assert ctypes.sizeof(cats.KVLayer) == 16
     assert ctypes.sizeof(cats.AcceptResult) == 4 * (1 + 17 + 17 + 1 + 1)
@@ -47,6 +47,6 @@ def test_null_arguments_are_rejected_before_any_device_work():
     assert lib.cats_set_tree(None, None, None) == cats.CATS_EINVAL
     assert lib.cats_verify_layer(None, None, None, None, 0, None) == cats.CATS_EINVAL
     assert lib.cats_tree_attention(None, None, None, 0, None, None) == cats.CATS_EINVAL
-    bad = cats.ModelDesc(2, 250, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0)   # hidden % 64 != 0
+    bad = cats.ModelDesc(2, 250, 4, 64, 688, 1024, 320, 128, 1e-6, 10000.0, 0)   # hidden % 64 != 0
     handle = ctypes.c_void_p()
     assert lib.cats_create(ctypes.byref(bad), ctypes.byref(handle)) == cats.CATS_EINVAL
