@@ -15,6 +15,7 @@ struct cats_ctx {
     int device;
     // uploaded tree (device) and its host copy
     int32_t *token, *parent, *depth;
+    u32x4* anc;  // [max_tree] ancestor-or-self masks of the uploaded tree
     int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
     int T;  // 0 = no tree set
     // scratch
@@ -71,9 +72,10 @@ int target_wgs() {
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    // aim at ~512 waves per launch (1024 SIMDs): heads * chunks * query groups
+    // aim at one wave per SIMD (1024 SIMDs; the kernel needs most of the register file):
+    // heads * chunks * query groups * waves per workgroup
     const int tq = (c->T + 31) / 32;
-    int chunks = std::max(1, 512 / std::max(1, c->d.n_heads * tq));
+    int chunks = std::max(1, 1024 / std::max(1, c->d.n_heads * tq * ATTN_WAVES));
     chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
     return (n_blocks + chunks - 1) / chunks;
 }
@@ -137,7 +139,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.out_lo = out_lo;
     a.kc = static_cast<const bf16_t*>(kv->k);
     a.vt = static_cast<const bf16_t*>(kv->v);
-    a.parent = c->parent;
+    a.anc = c->anc;
     a.T = c->T;
     a.H = c->d.hidden;
     a.nh = c->d.n_heads;
@@ -318,6 +320,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
         return o;
     };
     const size_t o_tok = take(Tm * 4), o_par = take(Tm * 4), o_dep = take(Tm * 4);
+    const size_t o_anc = take(Tm * sizeof(u32x4));
     const size_t o_x = take(Tm * H * 4), o_xn = take(Tm * H * 2), o_q = take(Tm * H * 2);
     const size_t o_attn = take(Tm * H * 2), o_h = take(Tm * F * 2);
     const size_t o_xn_lo = take(Tm * H * 2), o_q_lo = take(Tm * H * 2), o_attn_lo = take(Tm * H * 2);
@@ -343,6 +346,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->token = reinterpret_cast<int32_t*>(b + o_tok);
     c->parent = reinterpret_cast<int32_t*>(b + o_par);
     c->depth = reinterpret_cast<int32_t*>(b + o_dep);
+    c->anc = reinterpret_cast<u32x4*>(b + o_anc);
     c->x = reinterpret_cast<float*>(b + o_x);
     c->xn = reinterpret_cast<bf16_t*>(b + o_xn);
     c->q = reinterpret_cast<bf16_t*>(b + o_q);
@@ -395,6 +399,7 @@ int cats_set_tree(cats_ctx* ctx, const cats_tree* tree, void* stream) {
     std::memcpy(up.parent, tree->parent, sizeof(int32_t) * n);
     std::memcpy(up.depth, tree->depth, sizeof(int32_t) * n);
     launch_tree_upload(up, n, ctx->token, ctx->parent, ctx->depth, as_stream(stream));
+    launch_tree_masks(ctx->parent, n, ctx->anc, as_stream(stream));
     HIP_TRY(hipGetLastError());
     std::memcpy(ctx->h_parent, tree->parent, sizeof(int32_t) * n);
     std::memcpy(ctx->h_depth, tree->depth, sizeof(int32_t) * n);

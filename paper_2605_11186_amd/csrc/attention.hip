@@ -2,10 +2,12 @@
 // right-lower: the tree attention mask; Sec. 3.2 "Target verification pass").
 //
 // Node i attends to cache rows [0, ctx_len) and to rows ctx_len + a for every a
-// on its root-to-node path.  The ancestor sets are built inside the kernel from
-// parent[] (staged in LDS) as 128-bit masks.
+// on its root-to-node path.  The ancestor sets are 128-bit masks, built from parent[] in
+// LDS by cats_tree_masks when the tree is uploaded and read here one mask per query.
 //
-// Work split: one wave per (head, chunk of key blocks, group of 32 queries).
+// Work split: one workgroup of ATTN_WAVES waves per (head, chunk of key blocks, group of
+// 32 queries); wave w takes the chunk's blocks w, w + ATTN_WAVES, ... and the waves'
+// partial results are merged through LDS before the chunk's result is written.
 // Scores are computed transposed, S^T = K Q^T, with the 16x16x32 bf16 MFMA, so a
 // lane owns ONE query column and 8 keys of every 32-key block: the running
 // max / sum of the online softmax are per-lane scalars shared by four lanes and
@@ -23,33 +25,24 @@ namespace {
 // k = 8*(l/16)..+7; for B, column l%16 and the same k; its 4 results are
 // D[4*(l/16) + r][l%16].
 template <int D>
-__global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
+__global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_partial(AttnArgs a) {
     constexpr int KS = D / 32;  // k-steps of the score product
     constexpr int DB = D / 16;  // 16-row blocks of O^T
-    __shared__ int32_t s_parent[CATS_MAX_TREE];
+    __shared__ float s_o[ATTN_WAVES][32][D + 4];
+    __shared__ float s_ml[ATTN_WAVES][32][2];
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, q4 = lane >> 4;
     const int chunk = blockIdx.x, h = blockIdx.y, qbase = blockIdx.z * 32;
     const int S = a.ctx_len, T = a.T;
     const int n_keys = S + T;
 
-    for (int i = lane; i < T; i += 64) s_parent[i] = a.parent[i];
-    __syncthreads();
-
     // ancestor-or-self masks of this lane's two queries
     u32x4 anc[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        anc[qb] = u32x4{0u, 0u, 0u, 0u};
-        int node = qbase + 16 * qb + m;
-        if (node >= T) node = -1;
-        for (int step = 0; step <= CATS_MAX_DEPTH && node >= 0; ++step) {
-            const uint32_t bit = 1u << (node & 31);
-            const int w = node >> 5;
-            anc[qb] |= u32x4{w == 0 ? bit : 0u, w == 1 ? bit : 0u, w == 2 ? bit : 0u, w == 3 ? bit : 0u};
-            node = s_parent[node];
-        }
+        const int node = qbase + 16 * qb + m;
+        anc[qb] = node < T ? a.anc[node] : u32x4{0u, 0u, 0u, 0u};
     }
 
     // Q^T fragments (B operand of the score product): column = query, k = dim; queries come
@@ -193,35 +186,83 @@ __global__ __launch_bounds__(64) void cats_tree_attention_partial(AttnArgs a) {
     // Two register sets: the fragments of block b+1 are requested before block b is
     // multiplied, so the cache latency of one block hides behind the arithmetic of the other.
     bf16x8 kfA[2][KS], kfB[2][KS], vfA[DB], vfB[DB];
-    if (blk_begin < blk_end) {
-        load_block(kfA, vfA, blk_begin);
-        for (int blk = blk_begin; blk < blk_end; blk += 2) {
-            load_block(kfB, vfB, min(blk + 1, blk_end - 1));
+    const int my_begin = blk_begin + wave;
+    if (my_begin < blk_end) {
+        const int last = my_begin + (blk_end - 1 - my_begin) / ATTN_WAVES * ATTN_WAVES;  // this wave's last block
+        load_block(kfA, vfA, my_begin);
+        for (int blk = my_begin; blk < blk_end; blk += 2 * ATTN_WAVES) {
+            load_block(kfB, vfB, min(blk + ATTN_WAVES, last));
             compute_block(kfA, vfA, blk);
-            if (blk + 1 < blk_end) {
-                load_block(kfA, vfA, min(blk + 2, blk_end - 1));
-                compute_block(kfB, vfB, blk + 1);
+            if (blk + ATTN_WAVES < blk_end) {
+                load_block(kfA, vfA, min(blk + 2 * ATTN_WAVES, last));
+                compute_block(kfB, vfB, blk + ATTN_WAVES);
             }
         }
     }
 
-    // partial results of this chunk
+    // every wave parks its running max, row sum and unnormalised output in LDS ...
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         float l = lrun[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        const int t = qbase + 16 * qb + m;
-        const size_t slot = (static_cast<size_t>(h) * a.n_chunks + chunk) * a.t_pad + t;
-        float* po = a.po + slot * D;
+        const int ql = 16 * qb + m;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-            *reinterpret_cast<f32x4*>(po + 16 * db + 4 * q4) = o[qb][db];
+            *reinterpret_cast<f32x4*>(&s_o[wave][ql][16 * db + 4 * q4]) = o[qb][db];
         if (q4 == 0) {
-            a.pml[slot * 2] = mrun[qb];
+            s_ml[wave][ql][0] = mrun[qb];
+            s_ml[wave][ql][1] = l;
+        }
+    }
+    __syncthreads();
+    // ... and the workgroup merges them (fixed wave order) into the chunk's partial result:
+    // thread -> (query ql, D/8 consecutive dims)
+    {
+        const int ql = threadIdx.x >> 3, d0 = (threadIdx.x & 7) * (D / 8);
+        float M = -1e30f;
+#pragma unroll
+        for (int w = 0; w < ATTN_WAVES; ++w) M = fmaxf(M, s_ml[w][ql][0]);
+        float wgt[ATTN_WAVES], l = 0.f;
+#pragma unroll
+        for (int w = 0; w < ATTN_WAVES; ++w) {
+            wgt[w] = __expf(s_ml[w][ql][0] - M);
+            l += wgt[w] * s_ml[w][ql][1];
+        }
+        const size_t slot = (static_cast<size_t>(h) * a.n_chunks + chunk) * a.t_pad + qbase + ql;
+        float* po = a.po + slot * D + d0;
+#pragma unroll
+        for (int e = 0; e < D / 8; e += 4) {
+            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < ATTN_WAVES; ++w)
+                acc += wgt[w] * *reinterpret_cast<const f32x4*>(&s_o[w][ql][d0 + e]);
+            *reinterpret_cast<f32x4*>(po + e) = acc;
+        }
+        if ((threadIdx.x & 7) == 0) {
+            a.pml[slot * 2] = M;
             a.pml[slot * 2 + 1] = l;
         }
     }
+}
+
+// Ancestor-or-self set of every node as a 128-bit mask (bit a of anc[i] set when a is on the
+// path root..i): the tree attention mask in compact form.  One workgroup, parent[] in LDS.
+__global__ __launch_bounds__(CATS_MAX_TREE) void cats_tree_masks(const int32_t* parent, int T, u32x4* anc) {
+    __shared__ int32_t s_parent[CATS_MAX_TREE];
+    const int i = threadIdx.x;
+    if (i < T) s_parent[i] = parent[i];
+    __syncthreads();
+    if (i >= T) return;
+    u32x4 mask = u32x4{0u, 0u, 0u, 0u};
+    int node = i;
+    for (int step = 0; step <= CATS_MAX_DEPTH && node >= 0; ++step) {
+        const uint32_t bit = 1u << (node & 31);
+        const int w = node >> 5;
+        mask |= u32x4{w == 0 ? bit : 0u, w == 1 ? bit : 0u, w == 2 ? bit : 0u, w == 3 ? bit : 0u};
+        node = s_parent[node];
+    }
+    anc[i] = mask;
 }
 
 // out[t][h*D + dd] = sum_c exp(m_c - M) O_c[dd] / sum_c exp(m_c - M) l_c
@@ -249,13 +290,17 @@ __global__ void cats_tree_attention_merge(AttnArgs a) {
 
 }  // namespace
 
+void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st) {
+    hipLaunchKernelGGL(cats_tree_masks, dim3(1), dim3(CATS_MAX_TREE), 0, st, parent, T, anc);
+}
+
 void launch_attention(const AttnArgs& a, hipStream_t st) {
     dim3 grid(a.n_chunks, a.nh, a.t_pad / 32);
     if (a.d == 128) {
-        hipLaunchKernelGGL(cats_tree_attention_partial<128>, grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_partial<128>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
         hipLaunchKernelGGL(cats_tree_attention_merge<128>, dim3(a.T, a.nh), dim3(128), 0, st, a);
     } else {
-        hipLaunchKernelGGL(cats_tree_attention_partial<64>, grid, dim3(64), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_partial<64>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
         hipLaunchKernelGGL(cats_tree_attention_merge<64>, dim3(a.T, a.nh), dim3(64), 0, st, a);
     }
 }

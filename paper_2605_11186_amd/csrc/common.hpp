@@ -193,7 +193,7 @@ struct AttnArgs {
     const bf16_t* q_lo;     // optional [T][H] low parts of q
     const bf16_t* kc;       // [nh][max_ctx][d]
     const bf16_t* vt;       // [nh][d][max_ctx]
-    const int32_t* parent;  // device [T]
+    const u32x4* anc;       // device [T] ancestor-or-self masks (cats_tree_masks)
     int T, H, nh, d, max_ctx, ctx_len;
     int blocks_per_chunk, n_chunks, t_pad;
     float* po;              // [nh][n_chunks][t_pad][d]
@@ -201,7 +201,9 @@ struct AttnArgs {
     bf16_t* out;            // [T][H]
     bf16_t* out_lo;         // optional [T][H] low parts of the output
 };
-constexpr int ATTN_KB = 32;  // keys per block
+constexpr int ATTN_KB = 32;    // keys per block
+constexpr int ATTN_WAVES = 4;  // waves per attention workgroup, each taking every 4th block
+void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st);
 void launch_attention(const AttnArgs& a, hipStream_t st);
 
 // ---------------------------------------------------------------- accept / compact
