@@ -169,6 +169,13 @@ def main():
     offload = wl.get("offload", False)
     max_ctx = (S + T + (iterate * 9 if iterate else 0) + 63) // 64 * 64
     tok = synth.distinct_sibling_tokens(parent, dims.vocab, seed)
+    golden = None
+    gfile = ROOT / "tests" / "golden" / "config2_tree_7b.txt"
+    if args.workload == "7b_t63_s1024" and seed == 11186 and not args.tree_nodes and not args.ctx and gfile.exists():
+        # draft ids chosen by the CPU oracle from perturbed true logits, and the accept result it expects
+        golden = {k.strip(): v.split() for k, v in
+                  (l.split(":", 1) for l in gfile.read_text().splitlines() if l and not l.startswith("#"))}
+        tok = np.array(golden["tokens"], dtype=np.int32)
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -288,7 +295,11 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": wl["label"], "key": args.workload, "tree_nodes": T, "ctx_len": S,
-                   "layers": L, "seed": seed, "accepted_per_step": accepted["n_accepted"]},
+                   "layers": L, "seed": seed, "accepted_per_step": accepted["n_accepted"],
+                   "accept_matches_cpu_oracle": None if golden is None else bool(
+                       accepted["n_accepted"] == int(golden["n_accepted"][0])
+                       and accepted["path"] == [int(v) for v in golden["path"]]
+                       and accepted["bonus_token"] == int(golden["bonus_token"][0]))},
         "step_hbm": {"algorithmic_bytes": w_bytes + kv_bytes, "weight_bytes": w_bytes, "kv_bytes": kv_bytes,
                      "achieved_gbs": round(step_gbs, 1), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
         "roofline": {"bound": "hbm", "kernel": cats.cats_gemm_kernel_name(),

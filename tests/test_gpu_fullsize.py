@@ -7,6 +7,8 @@ sampled nodes are recomputed one by one by the oracle's plain token-at-a-time
 decoder over their own root-to-node paths.  Smaller-depth runs cover the 13B
 layer shape and the 128-node tree (the widest accumulator variant of the GEMM).
 """
+from pathlib import Path
+
 import numpy as np
 import pytest
 import torch
@@ -78,15 +80,29 @@ def compare_with_oracle(pair, S, tok, parent, depth, kv_seed, check_paths=()):
     return g_acc
 
 
+def read_golden_tree():
+    """tests/golden/config2_tree_7b.txt: draft ids and the accept result of the CPU oracle
+    (written by tests/golden/make_config2_tree.py from the oracle and the seeded inputs only)."""
+    text = (Path(__file__).parent / "golden" / "config2_tree_7b.txt").read_text()
+    return {k.strip(): v.split() for k, v in
+            (l.split(":", 1) for l in text.splitlines() if l and not l.startswith("#"))}
+
+
 def test_7b_full_verify_step_matches_oracle():
+    """The benchmark's own workload: same weights, context rows and draft ids as bench.py."""
     dims = synth.V7B
     parent, depth, _ = synth.product_tree_pruned()
     T, S = len(parent), 1024
+    golden = read_golden_tree()
+    tok = np.array(golden["tokens"], dtype=np.int32)
     pair = Pair(dims, BENCH_SEED, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", packed=True)
     try:
-        tok = synth.distinct_sibling_tokens(parent, dims.vocab, BENCH_SEED)
-        deep = int(np.flatnonzero(depth == 3)[0])
-        compare_with_oracle(pair, S, tok, parent, depth, BENCH_SEED, check_paths=(0, deep))
+        path = [int(v) for v in golden["path"]]
+        acc = compare_with_oracle(pair, S, tok, parent, depth, BENCH_SEED, check_paths=(0, path[-1]))
+        # the stored expectation (every decision on the accepted path has a margin > 4e-2)
+        assert float(golden["min_margin_on_path"][0]) > MARGIN
+        assert acc["n_accepted"] == int(golden["n_accepted"][0]) == 4
+        assert acc["path"] == path and acc["bonus_token"] == int(golden["bonus_token"][0])
     finally:
         pair.close()
 
