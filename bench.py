@@ -34,6 +34,8 @@ WORKLOADS = {
     "7b_offload_t128_s1024": dict(model="V7B", ctx=1024, tree="rand128", offload=True, label="7B-shape, layer weights in pinned host memory streamed through two HBM staging buffers, 128-node random tree, KV context 1024"),
     # BASELINE configs[3]: 100 consecutive verify-accept-compact iterations
     "13b_t64_s2048_x100": dict(model="V13B", ctx=2048, tree="rand64d7", iterate=100, label="13B-shape (40L, H5120, F13824), 100 verify-accept-compact iterations, 64-node trees (depth 7), KV context from 2048"),
+    # BASELINE configs[2]: tree-size and context sweep on the 7B shape
+    "7b_sweep": dict(model="V7B", ctx=4096, tree="rand128", sweep=True, label="7B-shape sweep: tree sizes 16/32/64/128 (random parents, depth<=8) x KV context 512/2048/4096"),
     "tiny": dict(model="TINY", ctx=128, tree="binary15", label="tiny oracle-check model, 15-node binary tree, KV context 128"),
 }
 
@@ -229,6 +231,51 @@ def main():
         else:
             cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"], d_final["w_lm"],
                                   kv_arr, S, res_dev, stream=stream)
+
+    if wl.get("sweep"):
+        points = []
+        for Ts in (16, 32, 64, 128):
+            p_s, d_s = synth.random_tree(Ts, 8, 1)
+            tok_s = synth.distinct_sibling_tokens(p_s, dims.vocab, seed)
+            for Ss in (512, 2048, 4096):
+                def step_s():
+                    cats.cats_set_tree(ctx, tok_s, p_s, d_s, stream)
+                    cats.cats_verify_tree(ctx, layers_arr, 0, L, d_embed, None, d_final["g_final"],
+                                          d_final["w_lm"], kv_arr, Ss, res_dev, stream=stream)
+                for _ in range(args.warmup):
+                    step_s()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(args.steps):
+                    step_s()
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t1) / args.steps * 1e3
+                cats.cats_profile_gemm(ctx, True)
+                g_ms, g_n = 0.0, 0
+                for _ in range(max(1, args.steps // 5)):
+                    step_s()
+                    a_ms, a_n = cats.cats_profile_gemm_read(ctx)
+                    g_ms += a_ms
+                    g_n += a_n
+                cats.cats_profile_gemm(ctx, False)
+                wb, kvb = algorithmic_bytes(dims, Ts, Ss, L)
+                gemm_tbs = wb * (g_n / 129) / (g_ms * 1e-3) / 1e12
+                # bf16 MFMA work of the GEMMs: 2 flop per weight per node, twice for the hi+lo activation parts
+                mfma_util = (2 * 2 * Ts * (wb / 2) * (g_n / 129)) / (g_ms * 1e-3) / 2.5e15
+                points.append({"T": Ts, "S": Ss, "ms_per_step": round(ms, 3), "steps_per_s": round(1e3 / ms, 1),
+                               "step_gbs": round((wb + kvb) / (ms * 1e-3) / 1e9, 1),
+                               "gemm_weight_tbs": round(gemm_tbs, 3), "gemm_frac_of_hbm_peak": round(gemm_tbs / 8, 4),
+                               "gemm_mfma_frac_of_bf16_peak": round(mfma_util, 4)})
+        cats.cats_destroy(ctx)
+        best = max(points, key=lambda q: q["steps_per_s"])
+        print(json.dumps({"metric": "tree-verify steps/sec", "value": best["steps_per_s"], "unit": "steps/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": wl["label"], "key": args.workload, "layers": L, "seed": seed,
+                                     "value_is": "fastest point of the sweep"},
+                          "sweep": points}))
+        return
 
     if iterate:
         out = run_iterations(args, wl, dims, cats, synth, torch, np, ctx, layers_arr, kv_arr, d_embed, d_final,

@@ -95,6 +95,23 @@ GemmPlan make_gemm_plan(int N, int K, int target_wgs);
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
+// Sum of `pieces` 16-byte groups p[s * stride] (fixed order).  Loads go out in batches of eight
+// independent loads (indices past the end are clamped and masked), so a reader waits for one
+// memory round trip per batch instead of one per piece.
+__device__ __forceinline__ f32x4 sum_pieces4(const float* p, size_t stride, int pieces) {
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < pieces; s0 += 8) {
+        f32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            v[i] = *reinterpret_cast<const f32x4*>(p + static_cast<size_t>(min(s0 + i, pieces - 1)) * stride);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (s0 + i < pieces) acc += v[i];
+    }
+    return acc;
+}
+
 // Sum of the pieces of column n of row t (fixed order).
 __device__ __forceinline__ float sum_pieces(const float* part, const GemmPlan& p, int T, int N, int t, int n) {
     const int pieces = plan_pieces(p, n / p.bn);

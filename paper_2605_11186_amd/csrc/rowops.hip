@@ -32,11 +32,7 @@ __global__ __launch_bounds__(64) void cats_residual_rmsnorm(ResidualNormArgs a) 
             val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
         }
         if (a.part) {
-            const float* pp = a.part + row + j;
-            const size_t stride = static_cast<size_t>(a.T) * a.H;
-            const int pieces = plan_pieces(a.plan, j / a.plan.bn);
-#pragma unroll 8
-            for (int s = 0; s < pieces; ++s) val += *reinterpret_cast<const f32x4*>(pp + s * stride);
+            val += sum_pieces4(a.part + row + j, static_cast<size_t>(a.T) * a.H, plan_pieces(a.plan, j / a.plan.bn));
         }
         ss = val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         if (a.embed || a.x_in || a.part) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
@@ -68,17 +64,21 @@ __global__ void cats_rope_table(RopeTableArgs a) {
     a.cs[idx] = make_float2(static_cast<float>(cos(ang)), static_cast<float>(sin(ang)));
 }
 
-// Adds up q|k|v partials, rotates q and k (pairs j, j+d/2), writes q (high and low bf16
-// parts), appends the key row and the (transposed) value column of every node at cache row
-// ctx_len + t.  grid (T, groups of heads), block 256: one thread per (head, pair).
+// Adds up q|k|v partials, scales by the row's norm factor, rotates q and k (pairs j, j+d/2),
+// writes q (high and low bf16 parts), appends the key row and the (transposed) value column
+// of every node at cache row ctx_len + t.  One thread per (head, 4 consecutive pairs): all
+// piece loads are 16-byte loads issued in batches.  grid (T, groups of heads), block 256.
 __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
     const int half = a.d / 2;
-    const int heads_per_block = 256 / half;
-    const int t = blockIdx.x, h = blockIdx.y * heads_per_block + threadIdx.x / half, j = threadIdx.x % half;
+    const int threads_per_head = half / 4;
+    const int heads_per_block = 256 / threads_per_head;
+    const int t = blockIdx.x, h = blockIdx.y * heads_per_block + threadIdx.x / threads_per_head;
+    const int j = 4 * (threadIdx.x % threads_per_head);
     if (h >= a.nh) return;
     const int N = 3 * a.H;
-    float v6[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x4 v6[6];
     const int c0 = h * a.d + j;
+    const size_t stride = static_cast<size_t>(a.T) * N;
     // the three column groups of one head lie in three different row tiles; within a head
     // all columns share a tile (head_dim divides the tile height)
 #pragma unroll
@@ -86,71 +86,65 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         const int col = m * a.H + c0;
         const int pieces = plan_pieces(a.plan, col / a.plan.bn);
         const float* p = a.part + static_cast<size_t>(t) * N + col;
-        const size_t stride = static_cast<size_t>(a.T) * N;
-        for (int s = 0; s < pieces; ++s) {
-            v6[2 * m] += p[s * stride];
-            v6[2 * m + 1] += p[s * stride + half];
-        }
+        v6[2 * m] = sum_pieces4(p, stride, pieces);
+        v6[2 * m + 1] = sum_pieces4(p + half, stride, pieces);
     }
     const float rs = row_scale(a.ns, t);
 #pragma unroll
     for (int m = 0; m < 6; ++m) v6[m] *= rs;
-    const float2 cs = a.cs[t * half + j];
-    const float q0 = v6[0] * cs.x - v6[1] * cs.y, q1 = v6[0] * cs.y + v6[1] * cs.x;
-    const float k0 = v6[2] * cs.x - v6[3] * cs.y, k1 = v6[2] * cs.y + v6[3] * cs.x;
-    const size_t qo = static_cast<size_t>(t) * a.H + h * a.d;
-    const bf16_t q0h = f2bf(q0), q1h = f2bf(q1);
-    a.q[qo + j] = q0h;
-    a.q[qo + j + half] = q1h;
-    a.q_lo[qo + j] = f2bf(q0 - bf2f(q0h));
-    a.q_lo[qo + j + half] = f2bf(q1 - bf2f(q1h));
+    const size_t qo = static_cast<size_t>(t) * a.H + c0;
     const int row = a.ctx_len + t;
-    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + row) * a.d;
-    k[j] = f2bf(k0);
-    k[j + half] = f2bf(k1);
+    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + row) * a.d + j;
     bf16_t* vt = a.vt + static_cast<size_t>(h) * a.d * a.max_ctx + row;
-    vt[static_cast<size_t>(j) * a.max_ctx] = f2bf(v6[4]);
-    vt[static_cast<size_t>(j + half) * a.max_ctx] = f2bf(v6[5]);
+    float q0[4], q1[4], k0[4], k1[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float2 cs = a.cs[t * half + j + e];
+        q0[e] = v6[0][e] * cs.x - v6[1][e] * cs.y;
+        q1[e] = v6[0][e] * cs.y + v6[1][e] * cs.x;
+        k0[e] = v6[2][e] * cs.x - v6[3][e] * cs.y;
+        k1[e] = v6[2][e] * cs.y + v6[3][e] * cs.x;
+        vt[static_cast<size_t>(j + e) * a.max_ctx] = f2bf(v6[4][e]);
+        vt[static_cast<size_t>(j + e + half) * a.max_ctx] = f2bf(v6[5][e]);
+    }
+    uint2 qh0, ql0, qh1, ql1;
+    split_bf2(q0[0], q0[1], qh0.x, ql0.x);
+    split_bf2(q0[2], q0[3], qh0.y, ql0.y);
+    split_bf2(q1[0], q1[1], qh1.x, ql1.x);
+    split_bf2(q1[2], q1[3], qh1.y, ql1.y);
+    *reinterpret_cast<uint2*>(a.q + qo) = qh0;
+    *reinterpret_cast<uint2*>(a.q_lo + qo) = ql0;
+    *reinterpret_cast<uint2*>(a.q + qo + half) = qh1;
+    *reinterpret_cast<uint2*>(a.q_lo + qo + half) = ql1;
+    *reinterpret_cast<uint2*>(k) = make_uint2(pack_bf2(k0[0], k0[1]), pack_bf2(k0[2], k0[3]));
+    *reinterpret_cast<uint2*>(k + half) = make_uint2(pack_bf2(k1[0], k1[1]), pack_bf2(k1[2], k1[3]));
 }
 
-// h[t][n] = silu(gate[t][n]) * up[t][n], two columns per thread, high and low bf16 parts
+// h[t][n] = silu(gate[t][n]) * up[t][n] after scaling both by the row's norm factor; four
+// columns per thread (16-byte piece loads in batches), high and low bf16 parts out.
 __global__ void cats_swiglu(SwigluArgs a) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    const int half_f = a.F / 2;
-    if (idx >= a.T * half_f) return;
-    const int t = idx / half_f, n = 2 * (idx - t * half_f);
+    const int quarter_f = a.F / 4;
+    if (idx >= a.T * quarter_f) return;
+    const int t = idx / quarter_f, n = 4 * (idx - t * quarter_f);
     const int N = 2 * a.f_pad;
-    float gt[2] = {0.f, 0.f}, up[2] = {0.f, 0.f};
     const size_t stride = static_cast<size_t>(a.T) * N;
-    {
-        const int pieces = plan_pieces(a.plan, n / a.plan.bn);  // n even: n and n+1 share a tile
-        const float* p = a.part + static_cast<size_t>(t) * N + n;
-        for (int s = 0; s < pieces; ++s) {
-            const float2 v = *reinterpret_cast<const float2*>(p + s * stride);
-            gt[0] += v.x;
-            gt[1] += v.y;
-        }
-    }
-    {
-        const int pieces = plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn);
-        const float* p = a.part + static_cast<size_t>(t) * N + a.f_pad + n;
-        for (int s = 0; s < pieces; ++s) {
-            const float2 v = *reinterpret_cast<const float2*>(p + s * stride);
-            up[0] += v.x;
-            up[1] += v.y;
-        }
-    }
+    const float* p = a.part + static_cast<size_t>(t) * N + n;
+    // n % 4 == 0 and the tile height is a multiple of 4: the four columns share a tile
+    f32x4 gt = sum_pieces4(p, stride, plan_pieces(a.plan, n / a.plan.bn));
+    f32x4 up = sum_pieces4(p + a.f_pad, stride, plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn));
     const float rs = row_scale(a.ns, t);
+    gt *= rs;
+    up *= rs;
+    float hv[4];
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        gt[m] *= rs;
-        up[m] *= rs;
-    }
-    uint32_t hi, lo;
-    split_bf2(gt[0] / (1.0f + __expf(-gt[0])) * up[0], gt[1] / (1.0f + __expf(-gt[1])) * up[1], hi, lo);
+    for (int e = 0; e < 4; ++e) hv[e] = gt[e] / (1.0f + __expf(-gt[e])) * up[e];
+    uint2 hi, lo;
+    split_bf2(hv[0], hv[1], hi.x, lo.x);
+    split_bf2(hv[2], hv[3], hi.y, lo.y);
     const size_t o = static_cast<size_t>(t) * a.F + n;
-    *reinterpret_cast<uint32_t*>(a.h + o) = hi;
-    *reinterpret_cast<uint32_t*>(a.h_lo + o) = lo;
+    *reinterpret_cast<uint2*>(a.h + o) = hi;
+    *reinterpret_cast<uint2*>(a.h_lo + o) = lo;
 }
 
 // Per node: add up the logits partials, optionally store them, find the largest
@@ -214,13 +208,13 @@ void launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
 }
 
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st) {
-    const int heads_per_block = 256 / (a.d / 2);
+    const int heads_per_block = 256 / (a.d / 8);
     hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T, (a.nh + heads_per_block - 1) / heads_per_block), dim3(256),
                        0, st, a);
 }
 
 void launch_swiglu(const SwigluArgs& a, hipStream_t st) {
-    const int n = a.T * (a.F / 2);
+    const int n = a.T * (a.F / 4);
     hipLaunchKernelGGL(cats_swiglu, dim3((n + 255) / 256), dim3(256), 0, st, a);
 }
 
