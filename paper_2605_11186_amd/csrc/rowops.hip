@@ -65,47 +65,74 @@ __global__ void cats_rope_table(RopeTableArgs a) {
 }
 
 // Adds up q|k|v partials, scales by the row's norm factor, rotates q and k (pairs j, j+d/2),
-// writes q (high and low bf16 parts), appends the key row and the (transposed) value column
-// of every node at cache row ctx_len + t.  One thread per (head, 4 consecutive pairs): all
-// piece loads are 16-byte loads issued in batches.  grid (T, groups of heads), block 256.
+// writes q (high and low bf16 parts) and appends the key row and the (transposed) value column
+// of every node at cache row ctx_len + t.  All piece loads are 16-byte loads issued in batches.
+// Blocks [0, T * gy): q and k, one thread per (node, head, 4 consecutive pairs).
+// Blocks after those: values, one block per (head, 32 dims): the sums go through LDS so that
+// the stores into the transposed cache run along the node index (contiguous in memory).
+constexpr int V_DIMS = 32;   // head dims per value block
 __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
+    __shared__ bf16_t s_v[V_DIMS][CATS_MAX_TREE + 2];
     const int half = a.d / 2;
+    const int N = 3 * a.H;
+    const size_t stride = static_cast<size_t>(a.T) * N;
     const int threads_per_head = half / 4;
     const int heads_per_block = 256 / threads_per_head;
-    const int t = blockIdx.x, h = blockIdx.y * heads_per_block + threadIdx.x / threads_per_head;
+    const int gy = (a.nh + heads_per_block - 1) / heads_per_block;
+    const int n_qk = a.T * gy;
+    if (static_cast<int>(blockIdx.x) >= n_qk) {
+        const int vb = blockIdx.x - n_qk, slices = a.d / V_DIMS;
+        const int h = vb / slices, ds = (vb - h * slices) * V_DIMS;
+        const int col = 2 * a.H + h * a.d + ds + 4 * (threadIdx.x & 7);
+        const int pieces = plan_pieces(a.plan, col / a.plan.bn);
+        for (int t0 = 0; t0 < a.T; t0 += 64) {   // two nodes per thread and pass
+            const int ta = t0 + (threadIdx.x >> 3), tb = ta + 32;
+            const int ca = min(ta, a.T - 1), cb = min(tb, a.T - 1);
+            f32x4 va = sum_pieces4(a.part + static_cast<size_t>(ca) * N + col, stride, pieces);
+            f32x4 vb4 = sum_pieces4(a.part + static_cast<size_t>(cb) * N + col, stride, pieces);
+            va *= row_scale(a.ns, ca);
+            vb4 *= row_scale(a.ns, cb);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (ta < a.T) s_v[4 * (threadIdx.x & 7) + e][ta] = f2bf(va[e]);
+                if (tb < a.T) s_v[4 * (threadIdx.x & 7) + e][tb] = f2bf(vb4[e]);
+            }
+        }
+        __syncthreads();
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        bf16_t* vt = a.vt + (static_cast<size_t>(h) * a.d + ds) * a.max_ctx + a.ctx_len;
+        for (int dd = wave; dd < V_DIMS; dd += 4)
+            for (int t = lane; t < a.T; t += 64) vt[static_cast<size_t>(dd) * a.max_ctx + t] = s_v[dd][t];
+        return;
+    }
+    const int t = blockIdx.x / gy, h = (blockIdx.x - t * gy) * heads_per_block + threadIdx.x / threads_per_head;
     const int j = 4 * (threadIdx.x % threads_per_head);
     if (h >= a.nh) return;
-    const int N = 3 * a.H;
-    f32x4 v6[6];
+    f32x4 v4[4];
     const int c0 = h * a.d + j;
-    const size_t stride = static_cast<size_t>(a.T) * N;
-    // the three column groups of one head lie in three different row tiles; within a head
-    // all columns share a tile (head_dim divides the tile height)
+    // the column groups of one head lie in different row tiles; within a head all columns
+    // share a tile (head_dim divides the tile height)
 #pragma unroll
-    for (int m = 0; m < 3; ++m) {
+    for (int m = 0; m < 2; ++m) {
         const int col = m * a.H + c0;
         const int pieces = plan_pieces(a.plan, col / a.plan.bn);
         const float* p = a.part + static_cast<size_t>(t) * N + col;
-        v6[2 * m] = sum_pieces4(p, stride, pieces);
-        v6[2 * m + 1] = sum_pieces4(p + half, stride, pieces);
+        v4[2 * m] = sum_pieces4(p, stride, pieces);
+        v4[2 * m + 1] = sum_pieces4(p + half, stride, pieces);
     }
     const float rs = row_scale(a.ns, t);
 #pragma unroll
-    for (int m = 0; m < 6; ++m) v6[m] *= rs;
+    for (int m = 0; m < 4; ++m) v4[m] *= rs;
     const size_t qo = static_cast<size_t>(t) * a.H + c0;
-    const int row = a.ctx_len + t;
-    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + row) * a.d + j;
-    bf16_t* vt = a.vt + static_cast<size_t>(h) * a.d * a.max_ctx + row;
+    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + a.ctx_len + t) * a.d + j;
     float q0[4], q1[4], k0[4], k1[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         const float2 cs = a.cs[t * half + j + e];
-        q0[e] = v6[0][e] * cs.x - v6[1][e] * cs.y;
-        q1[e] = v6[0][e] * cs.y + v6[1][e] * cs.x;
-        k0[e] = v6[2][e] * cs.x - v6[3][e] * cs.y;
-        k1[e] = v6[2][e] * cs.y + v6[3][e] * cs.x;
-        vt[static_cast<size_t>(j + e) * a.max_ctx] = f2bf(v6[4][e]);
-        vt[static_cast<size_t>(j + e + half) * a.max_ctx] = f2bf(v6[5][e]);
+        q0[e] = v4[0][e] * cs.x - v4[1][e] * cs.y;
+        q1[e] = v4[0][e] * cs.y + v4[1][e] * cs.x;
+        k0[e] = v4[2][e] * cs.x - v4[3][e] * cs.y;
+        k1[e] = v4[2][e] * cs.y + v4[3][e] * cs.x;
     }
     uint2 qh0, ql0, qh1, ql1;
     split_bf2(q0[0], q0[1], qh0.x, ql0.x);
@@ -209,8 +236,8 @@ void launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
 
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st) {
     const int heads_per_block = 256 / (a.d / 8);
-    hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T, (a.nh + heads_per_block - 1) / heads_per_block), dim3(256),
-                       0, st, a);
+    const int gy = (a.nh + heads_per_block - 1) / heads_per_block;
+    hipLaunchKernelGGL(cats_qkv_rope_append, dim3(a.T * gy + a.nh * (a.d / V_DIMS)), dim3(256), 0, st, a);
 }
 
 void launch_swiglu(const SwigluArgs& a, hipStream_t st) {
