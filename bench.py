@@ -36,6 +36,10 @@ WORKLOADS = {
     "13b_t64_s2048_x100": dict(model="V13B", ctx=2048, tree="rand64d7", iterate=100, label="13B-shape (40L, H5120, F13824), 100 verify-accept-compact iterations, 64-node trees (depth 7), KV context from 2048"),
     # BASELINE configs[2]: tree-size and context sweep on the 7B shape
     "7b_sweep": dict(model="V7B", ctx=4096, tree="rand128", sweep=True, label="7B-shape sweep: tree sizes 16/32/64/128 (random parents, depth<=8) x KV context 512/2048/4096"),
+    # the cascaded cycle's own tree shape (Alg. 1): a draft chain of 5 plus correction leaves, shallow layers
+    # first (chain, then corrections alone), the remaining layers on the whole tree from hidden states
+    "7b_cascade_g5": dict(model="V7B", ctx=1024, tree="cascade", cascade=dict(gamma=5, l_sv=8, corr=(1, 3)),
+                          label="7B-shape cascaded cycle: draft chain of 5 + 2 correction leaves (8 nodes); layers 0..7 on the chain, then on the corrections alone, layers 8..31 + LM head on the tree; KV context 1024"),
     "tiny": dict(model="TINY", ctx=128, tree="binary15", label="tiny oracle-check model, 15-node binary tree, KV context 128"),
 }
 
@@ -157,7 +161,17 @@ def main():
     wl = dict(WORKLOADS[args.workload])
     dims = getattr(synth, wl["model"])
     S = args.ctx or wl["ctx"]
-    if args.tree_nodes:
+    cascade = wl.get("cascade")
+    if cascade:
+        rng = np.random.default_rng(args.seed)
+        drafts = rng.integers(0, dims.vocab, cascade["gamma"]).astype(np.int32)
+        corrections = np.full(cascade["gamma"], -1, dtype=np.int32)
+        for i in cascade["corr"]:
+            corrections[i] = (drafts[i] + 1 + rng.integers(0, dims.vocab - 1)) % dims.vocab
+        root = int(rng.integers(0, dims.vocab))
+        casc_tok, parent, depth, _ = cats.cats_build_tree(root, drafts, corrections)
+        casc_chain = cats.cats_build_tree(root, drafts)[:3]
+    elif args.tree_nodes:
         parent, depth = synth.random_tree(args.tree_nodes, 8, 1)
         wl["label"] += f" [override: {args.tree_nodes}-node random tree]"
     else:
@@ -170,7 +184,7 @@ def main():
     iterate = wl.get("iterate", 0)
     offload = wl.get("offload", False)
     max_ctx = (S + T + (iterate * 9 if iterate else 0) + 63) // 64 * 64
-    tok = synth.distinct_sibling_tokens(parent, dims.vocab, seed)
+    tok = casc_tok if cascade else synth.distinct_sibling_tokens(parent, dims.vocab, seed)
     golden = None
     gfile = ROOT / "tests" / "golden" / "config2_tree_7b.txt"
     if args.workload == "7b_t63_s1024" and seed == 11186 and not args.tree_nodes and not args.ctx and gfile.exists():
@@ -275,6 +289,49 @@ def main():
                           "config": {"workload": wl["label"], "key": args.workload, "layers": L, "seed": seed,
                                      "value_is": "fastest point of the sweep"},
                           "sweep": points}))
+        return
+
+    if cascade:
+        g, l_sv = cascade["gamma"], cascade["l_sv"]
+        h_sv = torch.empty(T, dims.hidden, dtype=torch.float32, device=dev)
+        amax = torch.empty(T, dtype=torch.int32, device=dev)
+
+        def cycle():
+            cats.cats_set_tree(ctx, *casc_chain, stream)
+            cats.cats_verify_nodes(ctx, layers_arr, 0, l_sv, d_embed, None, kv_arr, S, 0, h_sv[: g + 1], stream)
+            cats.cats_set_tree(ctx, tok, parent, depth, stream)
+            cats.cats_verify_nodes(ctx, layers_arr, 0, l_sv, d_embed, None, kv_arr, S, g + 1, h_sv[g + 1:], stream)
+            cats.cats_verify_tree(ctx, layers_arr, l_sv, L, None, h_sv, d_final["g_final"], d_final["w_lm"],
+                                  kv_arr, S, res_dev, argmax_out=amax, stream=stream)
+            cats.cats_accept_and_compact(ctx, amax, kv_arr, 0, l_sv, S, res_dev, stream=stream)
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t1) / args.steps * 1e3
+
+        ms_cycle = timed(cycle)
+        acc_staged = cats.accept_result_from_tensor(res_dev)
+        ms_one_shot = timed(step)
+        acc_one = cats.accept_result_from_tensor(res_dev)
+        w_layer = dims.layer_weight_elems() * 2
+        w_bytes = (L + l_sv) * w_layer + dims.vocab * dims.hidden * 2   # shallow layers are streamed twice
+        cats.cats_destroy(ctx)
+        print(json.dumps({"metric": "tree-verify steps/sec", "value": round(1e3 / ms_cycle, 3), "unit": "steps/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(ms_cycle, 4), "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": wl["label"], "key": args.workload, "tree_nodes": T, "ctx_len": S,
+                                     "layers": L, "l_sv": l_sv, "seed": seed},
+                          "cascade": {"weight_bytes_streamed": w_bytes,
+                                      "weight_gbs": round(w_bytes / (ms_cycle * 1e-3) / 1e9, 1),
+                                      "one_shot_same_tree_ms": round(ms_one_shot, 4),
+                                      "staged_equals_one_shot_accept": acc_staged == acc_one}}))
         return
 
     if iterate:

@@ -44,7 +44,7 @@ extern "C" {
 typedef enum {
     CATS_OK = 0,
     CATS_EINVAL = -1,    /* null pointer, bad shape, malformed tree, token out of range */
-    CATS_ECAPACITY = -2, /* ctx_len + T exceeds max_ctx                                  */
+    CATS_ECAPACITY = -2, /* ctx_len + T exceeds max_ctx, or a tree exceeds its arrays       */
     CATS_ESTATE = -3,    /* no tree has been set                                         */
     CATS_EHIP = -4       /* a HIP runtime call failed                                    */
 } cats_status;
@@ -161,6 +161,39 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
                      int32_t ctx_len, float *hidden_out, float *logits_out, int32_t *argmax_out,
                      float *margin_out, cats_accept_result *out_dev, cats_accept_result *out_host,
                      void *stream);
+
+/* Shallow-verification stage, correction re-forward (Sec. 3.2 "shallow verification"; Alg. 1,
+ * stage 2: the correction tokens are forwarded again through the resident layers under the tree
+ * mask while the main draft chain is not).  Forwards only nodes [node_begin, T) of the tree set
+ * by cats_set_tree through layers [layer_begin, layer_end): their queries see the KV context and
+ * their ancestors; their K/V rows are written at cache rows ctx_len + node.  The K/V rows of the
+ * ancestors among nodes [0, node_begin) must already be in those layers' caches at rows
+ * ctx_len + node (left there by an earlier cats_verify_tree / cats_verify_nodes call on a tree
+ * whose first node_begin nodes were the same, without compaction in between).
+ * Input rows: embedding lookup of the nodes' tokens when `embed` is given, else hidden_in
+ * float32 [T - node_begin][hidden] (DEVICE).  hidden_out: DEVICE float32 [T - node_begin][hidden],
+ * the residual stream of those nodes after layer layer_end - 1 (required).  No LM head, no
+ * acceptance: stage 3 (cats_verify_tree over the remaining layers with hidden_in) does that.
+ * CATS_EINVAL for node_begin outside [0, T). */
+int cats_verify_nodes(cats_ctx *ctx, const cats_layer_weights *layers, int32_t layer_begin,
+                      int32_t layer_end, const void *embed, const float *hidden_in,
+                      const cats_kv_layer *kv, int32_t ctx_len, int32_t node_begin,
+                      float *hidden_out, void *stream);
+
+/* Verification tree of one cascaded cycle (Alg. 1, stage 2: ChainTree / BuildTree; Fig. 4 right
+ * upper).  HOST arrays only, nothing is enqueued.  Node 0 carries root_token (the last committed
+ * token); draft position i (token main_tokens[i], i < gamma) is node i + 1, child of node i; every
+ * position whose corrections[i] is >= 0 and differs from main_tokens[i] adds one leaf carrying
+ * corrections[i] as a sibling of draft position i (child of node i), numbered after the chain in
+ * position order.  corrections may be NULL (plain chain).  Outputs token/parent/depth[capacity],
+ * *n_out = 1 + gamma + number of corrections, corr_node[gamma] (optional: node of the correction
+ * at each position, -1 where there is none).  Because the chain comes first, the corrections are
+ * exactly nodes [gamma + 1, n): the range cats_verify_nodes re-forwards.
+ * CATS_EINVAL: gamma outside [0, CATS_MAX_DEPTH] or a NULL output; CATS_ECAPACITY: more nodes
+ * than capacity or CATS_MAX_TREE. */
+int cats_build_tree(int32_t root_token, const int32_t *main_tokens, int32_t gamma,
+                    const int32_t *corrections, int32_t capacity, int32_t *token, int32_t *parent,
+                    int32_t *depth, int32_t *n_out, int32_t *corr_node);
 
 /* Offload regime (Sec. 3.2: the target layers are "streamed ... chunk by chunk" while the
  * previous chunk computes; Fig. 4 left): the same verify step with the layer weights held

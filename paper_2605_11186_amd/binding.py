@@ -14,7 +14,8 @@ import numpy as np
 __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWeights", "KVLayer",
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
-           "cats_accept_and_compact", "cats_verify_tree", "cats_lm_head_argmax",
+           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree",
+           "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
            "cats_verify_tree_streamed", "cats_layer_weight_bytes", "cats_packed_matrix_bytes",
            "cats_pack_matrix", "pack_layer", "MATRIX_FIELDS", "layer_weights_struct", "kv_array",
@@ -84,6 +85,10 @@ _SIGNATURES = {
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_void_p, C.c_void_p],
+    "cats_verify_nodes": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                          C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
+    "cats_build_tree": [C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                        C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_pack_matrix": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -209,6 +214,31 @@ def cats_verify_tree(ctx, layers_arr, layer_begin: int, layer_end: int, embed, h
         _dp(w_lm), kv_arr, int(ctx_len), _dp(hidden_out), _dp(logits_out), _dp(argmax_out),
         _dp(margin_out), _dp(out_dev), None if out_host is None else C.byref(out_host),
         _stream(stream)))
+
+
+def cats_verify_nodes(ctx, layers_arr, layer_begin: int, layer_end: int, embed, hidden_in, kv_arr,
+                      ctx_len: int, node_begin: int, hidden_out, stream=None):
+    _check(library().cats_verify_nodes(
+        ctx, layers_arr, int(layer_begin), int(layer_end), _dp(embed), _dp(hidden_in), kv_arr,
+        int(ctx_len), int(node_begin), _dp(hidden_out), _stream(stream)))
+
+
+def cats_build_tree(root_token: int, main_tokens, corrections=None, capacity: int = CATS_MAX_TREE):
+    """Host-side tree of one cascaded cycle: (token, parent, depth, corr_node) numpy int32 arrays."""
+    main = np.ascontiguousarray(main_tokens, dtype=np.int32)
+    gamma = len(main)
+    corr = None if corrections is None else np.ascontiguousarray(corrections, dtype=np.int32)
+    if corr is not None and len(corr) != gamma:
+        raise CatsError(CATS_EINVAL, "corrections must have one entry per draft position")
+    cap = max(int(capacity), 1)
+    token, parent, depth = (np.zeros(cap, dtype=np.int32) for _ in range(3))
+    corr_node = np.full(max(gamma, 1), -1, dtype=np.int32)
+    n = C.c_int32(0)
+    _check(library().cats_build_tree(
+        int(root_token), main.ctypes.data if gamma else None, gamma,
+        None if corr is None else corr.ctypes.data, int(capacity), token.ctypes.data, parent.ctypes.data,
+        depth.ctypes.data, C.byref(n), corr_node.ctypes.data))
+    return token[: n.value].copy(), parent[: n.value].copy(), depth[: n.value].copy(), corr_node[:gamma].copy()
 
 
 def cats_packed_matrix_bytes(rows: int, cols: int) -> int:

@@ -18,6 +18,7 @@ struct cats_ctx {
     u32x4* anc;  // [max_tree] ancestor-or-self masks of the uploaded tree
     int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
     int T;  // 0 = no tree set
+    int n0 = 0;  // first node of the range being forwarded (0 except inside cats_verify_nodes)
     // scratch
     float* x;        // [max_tree][H] residual stream
     // activations that feed a GEMM or the attention products: high and low bf16 parts
@@ -74,7 +75,7 @@ int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
     // aim at one wave per SIMD (1024 SIMDs; the kernel needs most of the register file):
     // heads * chunks * query groups * waves per workgroup
-    const int tq = (c->T + 31) / 32;
+    const int tq = (c->T - c->n0 + 31) / 32;
     int chunks = std::max(1, 1024 / std::max(1, c->d.n_heads * tq * ATTN_WAVES));
     chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
     return (n_blocks + chunks - 1) / chunks;
@@ -118,7 +119,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.packed = c->d.packed_weights;
     g.N = n_seg * g.seg_pad;
     g.K = K;
-    g.T = c->T;
+    g.T = c->T - c->n0;
     g.plan = make_gemm_plan(g.N, K, target_wgs());
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
@@ -141,6 +142,8 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.anc = c->anc;
     a.T = c->T;
+    a.Tq = c->T - c->n0;
+    a.q0 = c->n0;
     a.H = c->d.hidden;
     a.nh = c->d.n_heads;
     a.d = c->d.head_dim;
@@ -150,7 +153,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.blocks_per_chunk = attn_blocks_per_chunk(c, n_keys);
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
     a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
-    a.t_pad = (c->T + 31) / 32 * 32;
+    a.t_pad = (a.Tq + 31) / 32 * 32;
     a.po = c->attn_po;
     a.pml = c->attn_pml;
     a.out = out;
@@ -161,14 +164,14 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
 // exit x is updated and, if next_gain is given, c->xn holds rmsnorm(x)*next_gain.
 void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cats_kv_layer* kv,
                    int ctx_len, const void* next_gain, hipStream_t st) {
-    const int H = c->d.hidden, F = c->d.ffn, T = c->T;
+    const int H = c->d.hidden, F = c->d.ffn, T = c->T - c->n0;   // rows = nodes n0 .. T-1
     // attention block
     GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, 3, H, H, st);
     QkvRopeArgs qa;
     qa.part = c->part;
     qa.plan = plan;
     qa.ns = norm_scale(c);
-    qa.cs = c->rope_cs;
+    qa.cs = c->rope_cs + static_cast<size_t>(c->n0) * (c->d.head_dim / 2);
     qa.q = c->q;
     qa.q_lo = c->q_lo;
     qa.kc = static_cast<bf16_t*>(kv->k);
@@ -178,7 +181,7 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.nh = c->d.n_heads;
     qa.d = c->d.head_dim;
     qa.max_ctx = c->d.max_ctx;
-    qa.ctx_len = ctx_len;
+    qa.row0 = ctx_len + c->n0;
     launch_qkv_rope(qa, st);
     enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, st);
     plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
@@ -484,49 +487,115 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final,
     return CATS_OK;
 }
 
-int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
-                     const void* embed, const float* hidden_in, const void* g_final, const void* w_lm,
-                     const cats_kv_layer* kv, int32_t ctx_len, float* hidden_out, float* logits_out,
-                     int32_t* argmax_out, float* margin_out, cats_accept_result* out_dev,
-                     cats_accept_result* out_host, void* stream) {
-    const int rc = check_ctx_len(ctx, ctx_len);
-    if (rc != CATS_OK) return rc;
-    if (layer_begin < 0 || layer_end < layer_begin || layer_end > ctx->d.n_layers) return CATS_EINVAL;
-    if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;  // exactly one input source
-    if (!g_final || !w_lm || !out_dev) return CATS_EINVAL;
-    if (layer_end > layer_begin) {
-        if (!layers || !kv_ok(kv, layer_begin, layer_end)) return CATS_EINVAL;
-        for (int l = layer_begin; l < layer_end; ++l)
-            if (!layer_ok(&layers[l])) return CATS_EINVAL;
-    }
-    hipStream_t st = as_stream(stream);
-    const int T = ctx->T, H = ctx->d.hidden;
+// Rows n0..T-1 of the residual stream from the embedding table or from the caller's rows, plus
+// the first layer's normalised input; then layers [layer_begin, layer_end).
+static void enqueue_rows_and_layers(cats_ctx* ctx, const cats_layer_weights* layers, int layer_begin,
+                                    int layer_end, const void* embed, const float* hidden_in,
+                                    const void* last_gain, const cats_kv_layer* kv, int ctx_len,
+                                    hipStream_t st) {
     enqueue_rope_table(ctx, ctx_len, st);
     ResidualNormArgs rn;
     rn.x = ctx->x;
     rn.x_in = hidden_in;
     rn.embed = static_cast<const bf16_t*>(embed);
-    rn.token = ctx->token;
+    rn.token = ctx->token + ctx->n0;
     rn.part = nullptr;
     rn.plan = GemmPlan{1, 1, 1, 1};
-    rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : g_final);
+    rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : last_gain);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
     rn.ss = ctx->ss;
-    rn.T = T;
-    rn.H = H;
+    rn.T = ctx->T - ctx->n0;
+    rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
     launch_residual_norm(rn, st);
     for (int l = layer_begin; l < layer_end; ++l) {
-        const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : g_final;
+        const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : last_gain;
         enqueue_layer(ctx, &layers[l], ctx->x, &kv[l], ctx_len, next_gain, st);
     }
+}
+
+static int check_layer_range(const cats_ctx* ctx, const cats_layer_weights* layers, int layer_begin,
+                             int layer_end, const cats_kv_layer* kv) {
+    if (layer_begin < 0 || layer_end < layer_begin || layer_end > ctx->d.n_layers) return CATS_EINVAL;
+    if (layer_end > layer_begin) {
+        if (!layers || !kv_ok(kv, layer_begin, layer_end)) return CATS_EINVAL;
+        for (int l = layer_begin; l < layer_end; ++l)
+            if (!layer_ok(&layers[l])) return CATS_EINVAL;
+    }
+    return CATS_OK;
+}
+
+int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
+                     const void* embed, const float* hidden_in, const void* g_final, const void* w_lm,
+                     const cats_kv_layer* kv, int32_t ctx_len, float* hidden_out, float* logits_out,
+                     int32_t* argmax_out, float* margin_out, cats_accept_result* out_dev,
+                     cats_accept_result* out_host, void* stream) {
+    int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if ((rc = check_layer_range(ctx, layers, layer_begin, layer_end, kv)) != CATS_OK) return rc;
+    if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;  // exactly one input source
+    if (!g_final || !w_lm || !out_dev) return CATS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const int T = ctx->T, H = ctx->d.hidden;
+    enqueue_rows_and_layers(ctx, layers, layer_begin, layer_end, embed, hidden_in, g_final, kv, ctx_len, st);
     if (hidden_out)
         HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
     int32_t* amax = argmax_out ? argmax_out : ctx->amax;
     enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
     HIP_TRY(hipGetLastError());
     return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
+}
+
+int cats_verify_nodes(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
+                      const void* embed, const float* hidden_in, const cats_kv_layer* kv, int32_t ctx_len,
+                      int32_t node_begin, float* hidden_out, void* stream) {
+    int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if ((rc = check_layer_range(ctx, layers, layer_begin, layer_end, kv)) != CATS_OK) return rc;
+    if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;
+    if (node_begin < 0 || node_begin >= ctx->T || !hidden_out) return CATS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    ctx->n0 = node_begin;   // read by the enqueue helpers; reset before returning
+    enqueue_rows_and_layers(ctx, layers, layer_begin, layer_end, embed, hidden_in, nullptr, kv, ctx_len, st);
+    const size_t bytes = sizeof(float) * static_cast<size_t>(ctx->T - node_begin) * ctx->d.hidden;
+    ctx->n0 = 0;
+    HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, bytes, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
+int cats_build_tree(int32_t root_token, const int32_t* main_tokens, int32_t gamma, const int32_t* corrections,
+                    int32_t capacity, int32_t* token, int32_t* parent, int32_t* depth, int32_t* n_out,
+                    int32_t* corr_node) {
+    if (gamma < 0 || gamma > CATS_MAX_DEPTH || (gamma > 0 && !main_tokens) || !token || !parent || !depth || !n_out)
+        return CATS_EINVAL;
+    int n_corr = 0;
+    for (int i = 0; i < gamma; ++i)
+        if (corrections && corrections[i] >= 0 && corrections[i] != main_tokens[i]) ++n_corr;
+    const int n = 1 + gamma + n_corr;
+    if (n > capacity || n > CATS_MAX_TREE) return CATS_ECAPACITY;
+    token[0] = root_token;
+    parent[0] = -1;
+    depth[0] = 0;
+    for (int i = 0; i < gamma; ++i) {   // draft position i is node i+1, child of node i
+        token[i + 1] = main_tokens[i];
+        parent[i + 1] = i;
+        depth[i + 1] = i + 1;
+    }
+    int next = gamma + 1;
+    for (int i = 0; i < gamma; ++i) {   // a correction at position i is a sibling of draft position i
+        const bool has = corrections && corrections[i] >= 0 && corrections[i] != main_tokens[i];
+        if (has) {
+            token[next] = corrections[i];
+            parent[next] = i;
+            depth[next] = i + 1;
+        }
+        if (corr_node) corr_node[i] = has ? next : -1;
+        if (has) ++next;
+    }
+    *n_out = n;
+    return CATS_OK;
 }
 
 int cats_profile_gemm(cats_ctx* ctx, int enable) {
@@ -689,7 +758,7 @@ const char* cats_strerror(int status) {
     switch (status) {
         case CATS_OK: return "ok";
         case CATS_EINVAL: return "invalid argument (null pointer, bad shape, malformed tree or token out of range)";
-        case CATS_ECAPACITY: return "ctx_len + tree size exceeds max_ctx";
+        case CATS_ECAPACITY: return "capacity exceeded (ctx_len + tree size > max_ctx, or more nodes than the arrays hold)";
         case CATS_ESTATE: return "no tree has been set on this context";
         case CATS_EHIP: return hipGetErrorString(g_last_hip);
         default: return "unknown status";

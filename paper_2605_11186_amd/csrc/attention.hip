@@ -34,15 +34,15 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_partial(A
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, q4 = lane >> 4;
     const int chunk = blockIdx.x, h = blockIdx.y, qbase = blockIdx.z * 32;
-    const int S = a.ctx_len, T = a.T;
+    const int S = a.ctx_len, T = a.T, Tq = a.Tq;   // T tree nodes are keys; Tq of them (from q0) are queries
     const int n_keys = S + T;
 
     // ancestor-or-self masks of this lane's two queries
     u32x4 anc[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-        const int node = qbase + 16 * qb + m;
-        anc[qb] = node < T ? a.anc[node] : u32x4{0u, 0u, 0u, 0u};
+        const int t = qbase + 16 * qb + m;
+        anc[qb] = t < Tq ? a.anc[a.q0 + t] : u32x4{0u, 0u, 0u, 0u};
     }
 
     // Q^T fragments (B operand of the score product): column = query, k = dim; queries come
@@ -54,8 +54,8 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_partial(A
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             u32x4 v = u32x4{0u, 0u, 0u, 0u}, vl = u32x4{0u, 0u, 0u, 0u};
-            const size_t off = static_cast<size_t>(min(t, T - 1)) * a.H + h * D + 32 * s + 8 * q4;
-            if (t < T) {
+            const size_t off = static_cast<size_t>(min(t, Tq - 1)) * a.H + h * D + 32 * s + 8 * q4;
+            if (t < Tq) {
                 v = *reinterpret_cast<const u32x4*>(a.q + off);
                 if (a.q_lo) vl = *reinterpret_cast<const u32x4*>(a.q_lo + off);
             }
@@ -298,9 +298,9 @@ void launch_attention(const AttnArgs& a, hipStream_t st) {
     dim3 grid(a.n_chunks, a.nh, a.t_pad / 32);
     if (a.d == 128) {
         hipLaunchKernelGGL(cats_tree_attention_partial<128>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
-        hipLaunchKernelGGL(cats_tree_attention_merge<128>, dim3(a.T, a.nh), dim3(128), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_merge<128>, dim3(a.Tq, a.nh), dim3(128), 0, st, a);
     } else {
         hipLaunchKernelGGL(cats_tree_attention_partial<64>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
-        hipLaunchKernelGGL(cats_tree_attention_merge<64>, dim3(a.T, a.nh), dim3(64), 0, st, a);
+        hipLaunchKernelGGL(cats_tree_attention_merge<64>, dim3(a.Tq, a.nh), dim3(64), 0, st, a);
     }
 }

@@ -177,7 +177,8 @@ struct QkvRopeArgs {
     bf16_t* q_lo;       // [T][H] low parts
     bf16_t* kc;         // [nh][max_ctx][d]
     bf16_t* vt;         // [nh][d][max_ctx]
-    int T, H, nh, d, max_ctx, ctx_len;
+    int T, H, nh, d, max_ctx;
+    int row0;           // cache row of the first of the T rows (ctx_len + index of its node)
 };
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
 
@@ -206,17 +207,18 @@ void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
 
 // ---------------------------------------------------------------- attention
 struct AttnArgs {
-    const bf16_t* q;        // [T][H]
-    const bf16_t* q_lo;     // optional [T][H] low parts of q
+    const bf16_t* q;        // [Tq][H]
+    const bf16_t* q_lo;     // optional [Tq][H] low parts of q
     const bf16_t* kc;       // [nh][max_ctx][d]
     const bf16_t* vt;       // [nh][d][max_ctx]
     const u32x4* anc;       // device [T] ancestor-or-self masks (cats_tree_masks)
-    int T, H, nh, d, max_ctx, ctx_len;
+    int T, H, nh, d, max_ctx, ctx_len;   // T: tree nodes whose K/V rows ctx_len.. take part as keys
+    int Tq, q0;             // the queries are nodes q0 .. q0+Tq-1 (rows 0..Tq-1 of q / out)
     int blocks_per_chunk, n_chunks, t_pad;
     float* po;              // [nh][n_chunks][t_pad][d]
     float* pml;             // [nh][n_chunks][t_pad][2]
-    bf16_t* out;            // [T][H]
-    bf16_t* out_lo;         // optional [T][H] low parts of the output
+    bf16_t* out;            // [Tq][H]
+    bf16_t* out_lo;         // optional [Tq][H] low parts of the output
 };
 constexpr int ATTN_KB = 32;    // keys per block
 constexpr int ATTN_WAVES = 4;  // waves per attention workgroup, each taking every 4th block

@@ -66,7 +66,7 @@ __global__ void cats_rope_table(RopeTableArgs a) {
 
 // Adds up q|k|v partials, scales by the row's norm factor, rotates q and k (pairs j, j+d/2),
 // writes q (high and low bf16 parts) and appends the key row and the (transposed) value column
-// of every node at cache row ctx_len + t.  All piece loads are 16-byte loads issued in batches.
+// of row t at cache row row0 + t.  All piece loads are 16-byte loads issued in batches.
 // Blocks [0, T * gy): q and k, one thread per (node, head, 4 consecutive pairs).
 // Blocks after those: values, one block per (head, 32 dims): the sums go through LDS so that
 // the stores into the transposed cache run along the node index (contiguous in memory).
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         }
         __syncthreads();
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        bf16_t* vt = a.vt + (static_cast<size_t>(h) * a.d + ds) * a.max_ctx + a.ctx_len;
+        bf16_t* vt = a.vt + (static_cast<size_t>(h) * a.d + ds) * a.max_ctx + a.row0;
         for (int dd = wave; dd < V_DIMS; dd += 4)
             for (int t = lane; t < a.T; t += 64) vt[static_cast<size_t>(dd) * a.max_ctx + t] = s_v[dd][t];
         return;
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
 #pragma unroll
     for (int m = 0; m < 4; ++m) v4[m] *= rs;
     const size_t qo = static_cast<size_t>(t) * a.H + c0;
-    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + a.ctx_len + t) * a.d + j;
+    bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + a.row0 + t) * a.d + j;
     float q0[4], q1[4], k0[4], k1[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {

@@ -131,3 +131,20 @@ def test_7b_layer_shape_tree_and_context_sweep(T, S):
         compare_with_oracle(pair, S, tok, parent, depth, S)
     finally:
         pair.close()
+
+
+def test_7b_layer_shape_cascaded_cycle():
+    """The cascaded cycle's own small tree (draft chain of 5 + corrections) at the 7B layer shape:
+    shallow layer on the chain, then on the corrections alone, remaining layers on the tree."""
+    from test_gpu_cascade import check_cycle
+    dims = synth.V7B
+    S = 1024
+    pair = Pair(dims, 7, max_ctx=1088, max_tree=16, precision="f32", n_layers=3, packed=True)
+    try:
+        rng = np.random.default_rng(5)
+        drafts = rng.integers(0, dims.vocab, 5).astype(np.int32)
+        corrections = np.array([-1, (drafts[1] + 3) % dims.vocab, -1, (drafts[3] + 9) % dims.vocab, -1], np.int32)
+        kc, vc = pair.oracle_cache_random(S, S)
+        check_cycle(pair, kc, vc, S, 4242, drafts, corrections, 1)
+    finally:
+        pair.close()
