@@ -40,6 +40,9 @@ WORKLOADS = {
     # first (chain, then corrections alone), the remaining layers on the whole tree from hidden states
     "7b_cascade_g5": dict(model="V7B", ctx=1024, tree="cascade", cascade=dict(gamma=5, l_sv=8, corr=(1, 3)),
                           label="7B-shape cascaded cycle: draft chain of 5 + 2 correction leaves (8 nodes); layers 0..7 on the chain, then on the corrections alone, layers 8..31 + LM head on the tree; KV context 1024"),
+    # adapter-training side kernel (Eq. 2): not a verify step, its own metric and roofline
+    "reduced_kl_p4096_v32000_k10": dict(model="V7B", ctx=0, tree="binary15", loss=dict(P=4096, V=32000, K=10),
+                                        label="Reduced KL loss + gradient, 4096 positions x vocab 32000, top-10, LM-like seeded logits"),
     "tiny": dict(model="TINY", ctx=128, tree="binary15", label="tiny oracle-check model, 15-node binary tree, KV context 128"),
 }
 
@@ -134,6 +137,56 @@ def run_iterations(args, wl, dims, cats, synth, torch, np, ctx, layers_arr, kv_a
                            "note": "each step ends with a host read-back of the accept result"}}
 
 
+def bench_loss(args, wl, cats, synth, torch, np):
+    """Reduced KL loss (forward + gradient) over P positions: one launch of the per-position kernel
+    plus the mean; timed with HIP events on the launch stream."""
+    P, V, K = (wl["loss"][k] for k in ("P", "V", "K"))
+    rows = 256   # distinct seeded rows, tiled to P positions (generation time, not a property of the kernel)
+    a = torch.from_numpy(synth.lm_like_logits(args.seed, rows, V, tag=0)).cuda().repeat(P // rows, 1).contiguous()
+    z = torch.from_numpy(synth.lm_like_logits(args.seed, rows, V, tag=1)).cuda().repeat(P // rows, 1).contiguous()
+    loss = torch.zeros(1, device="cuda")
+    per_pos = torch.zeros(P, device="cuda")
+    topk = torch.zeros(P, K, dtype=torch.int32, device="cuda")
+    grad = torch.empty(P, V, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        cats.cats_reduced_kl_loss(a, z, K, loss, per_pos, topk_idx_out=topk, grad_out=grad, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ev[0].record(stream)
+    for _ in range(args.steps):
+        step()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t1) / args.steps * 1e3
+    ms_ev = ev[0].elapsed_time(ev[1]) / args.steps
+    alg = 3 * P * V * 4   # both logit rows read once, the gradient row written once
+    out = {"metric": "reduced-KL loss positions/sec", "value": round(P / (ms * 1e-3), 1), "unit": "positions/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": wl["label"], "key": args.workload, "positions": P, "vocab": V, "top_k": K,
+                      "seed": args.seed, "loss": round(loss.item(), 6)},
+           "roofline": {"bound": "hbm", "kernel": "cats_reduced_kl_positions", "achieved": round(alg / (ms_ev * 1e-3) / 1e9, 1),
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(alg / (ms_ev * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                        "traffic": None, "bytes_per_launch": alg, "avg_launch_us": round(ms_ev * 1e3, 2),
+                        "note": "events bracket the position kernel and the one-workgroup mean kernel together"}}
+    if not args.no_cpu_baseline:
+        from oracle import reduced_kl as rk
+        n = 32
+        a_h, z_h = a[:n].cpu().numpy(), z[:n].cpu().numpy()
+        t1 = time.perf_counter()
+        rk.reduced_kl_grad(a_h, z_h, K)
+        dt = time.perf_counter() - t1
+        out["cpu_baseline"] = {"value": round(n / dt, 2), "unit": "positions/s", "cores": 1, "kind": "oracle",
+                               "sample": f"float64 numpy oracle (loss + gradient) on the first {n} positions ({dt:.2f} s)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +212,8 @@ def main():
     import synth
 
     wl = dict(WORKLOADS[args.workload])
+    if wl.get("loss"):
+        return bench_loss(args, wl, cats, synth, torch, np)
     dims = getattr(synth, wl["model"])
     S = args.ctx or wl["ctx"]
     cascade = wl.get("cascade")

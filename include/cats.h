@@ -195,6 +195,27 @@ int cats_build_tree(int32_t root_token, const int32_t *main_tokens, int32_t gamm
                     const int32_t *corrections, int32_t capacity, int32_t *token, int32_t *parent,
                     int32_t *depth, int32_t *n_out, int32_t *corr_node);
 
+/* Reduced KL loss for adapter training (Sec. 3.3, Eq. 2; Appendix B steps 1-3) and its gradient.
+ * target_logits, draft_logits: DEVICE float32 [n_pos][vocab], row-major, 16-byte aligned;
+ * p_target and q_draft are their softmaxes.  Per position t with mask[t] != 0 (mask: DEVICE
+ * uint8 [n_pos], NULL = every position counts): T_K(t) = the top_k tokens of highest target
+ * probability (equal values: lower index first), p~ = p_target renormalised over T_K(t),
+ * loss_t = -sum_{v in T_K(t)} p~(v) log q_draft(v).
+ * Outputs (DEVICE): loss_out float32 [1] = mean of loss_t over the unmasked positions (0 if there
+ * is none); per_pos_out float32 [n_pos] = loss_t (0 where masked; required, it is also the
+ * workspace of the mean); topk_idx_out int32 [n_pos][top_k], optional: T_K(t) most probable
+ * first (-1 where masked); grad_out float32 [n_pos][vocab], optional, 16-byte aligned:
+ * d loss / d draft_logits = (q_draft - p~) / |M| (zero rows where masked).
+ * Logits must be finite.  Enqueues on `stream` and returns; nothing is allocated.
+ * CATS_EINVAL: NULL required pointer, misaligned pointer, n_pos < 1, vocab not a positive
+ * multiple of 4, top_k outside [1, min(CATS_LOSS_MAX_K, vocab)]; CATS_ECAPACITY: vocab above
+ * CATS_LOSS_MAX_VOCAB (the target row is kept in one workgroup's LDS). */
+#define CATS_LOSS_MAX_K 64
+#define CATS_LOSS_MAX_VOCAB 36864
+int cats_reduced_kl_loss(const float *target_logits, const float *draft_logits, const uint8_t *mask,
+                         int32_t n_pos, int32_t vocab, int32_t top_k, float *loss_out,
+                         float *per_pos_out, int32_t *topk_idx_out, float *grad_out, void *stream);
+
 /* Offload regime (Sec. 3.2: the target layers are "streamed ... chunk by chunk" while the
  * previous chunk computes; Fig. 4 left): the same verify step with the layer weights held
  * in pinned HOST memory.  host_layers: HOST array indexed by layer whose nine pointers are

@@ -14,7 +14,8 @@ import numpy as np
 __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWeights", "KVLayer",
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
-           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree",
+           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_reduced_kl_loss",
+           "CATS_LOSS_MAX_K", "CATS_LOSS_MAX_VOCAB",
            "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
            "cats_verify_tree_streamed", "cats_layer_weight_bytes", "cats_packed_matrix_bytes",
@@ -25,6 +26,8 @@ __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWe
 
 CATS_MAX_TREE = 128
 CATS_MAX_DEPTH = 16
+CATS_LOSS_MAX_K = 64
+CATS_LOSS_MAX_VOCAB = 36864
 CATS_OK, CATS_EINVAL, CATS_ECAPACITY, CATS_ESTATE, CATS_EHIP = 0, -1, -2, -3, -4
 
 _LIB_PATH = Path(__file__).resolve().parent / "libcats.so"
@@ -89,6 +92,8 @@ _SIGNATURES = {
                           C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
     "cats_build_tree": [C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                         C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_reduced_kl_loss": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_pack_matrix": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -239,6 +244,18 @@ def cats_build_tree(root_token: int, main_tokens, corrections=None, capacity: in
         None if corr is None else corr.ctypes.data, int(capacity), token.ctypes.data, parent.ctypes.data,
         depth.ctypes.data, C.byref(n), corr_node.ctypes.data))
     return token[: n.value].copy(), parent[: n.value].copy(), depth[: n.value].copy(), corr_node[:gamma].copy()
+
+
+def cats_reduced_kl_loss(target_logits, draft_logits, top_k: int, loss_out, per_pos_out, mask=None,
+                         topk_idx_out=None, grad_out=None, stream=None):
+    """Shapes are taken from target_logits [n_pos][vocab]; every tensor lives on the device."""
+    n_pos, vocab = target_logits.shape
+    for t in (target_logits, draft_logits, grad_out):
+        if t is not None and (tuple(t.shape) != (n_pos, vocab) or not t.is_contiguous()):
+            raise CatsError(CATS_EINVAL, "logit / gradient tensors must be contiguous [n_pos][vocab]")
+    _check(library().cats_reduced_kl_loss(
+        _dp(target_logits), _dp(draft_logits), _dp(mask), int(n_pos), int(vocab), int(top_k), _dp(loss_out),
+        _dp(per_pos_out), _dp(topk_idx_out), _dp(grad_out), _stream(stream)))
 
 
 def cats_packed_matrix_bytes(rows: int, cols: int) -> int:
