@@ -34,6 +34,8 @@ struct cats_ctx {
     float* attn_pml;
     int attn_max_chunks;
     int32_t* amax;   // [max_tree]
+    float *am_best, *am_second;   // [max_tree][ARGMAX_SLICES] slice results of the argmax
+    int *am_idx, *am_arrivals;    // [max_tree][ARGMAX_SLICES] indices, [max_tree] arrival counters (zero between launches)
     char* flat;      // the single allocation behind all of the above
     // offload regime: copy stream and the events that order it against the compute stream
     hipStream_t copy_stream;
@@ -241,6 +243,10 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
     am.ld = seg_pad_of(c, c->d.vocab);
     am.logits = logits_out;
     am.amax = argmax_out;
+    am.slice_best = c->am_best;
+    am.slice_second = c->am_second;
+    am.slice_idx = c->am_idx;
+    am.arrivals = c->am_arrivals;
     am.margin = margin_out;
     launch_argmax(am, st);
 }
@@ -334,6 +340,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
     const size_t o_pml = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * 2 * 4);
     const size_t o_amax = take(Tm * 4);
+    const size_t o_sb = take(Tm * ARGMAX_SLICES * 4), o_s2 = take(Tm * ARGMAX_SLICES * 4);
+    const size_t o_si = take(Tm * ARGMAX_SLICES * 4), o_arr = take(Tm * 4);   // zero from the memset below
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->flat), off);
     if (e != hipSuccess) {
         delete c;
@@ -365,6 +373,10 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->attn_po = reinterpret_cast<float*>(b + o_po);
     c->attn_pml = reinterpret_cast<float*>(b + o_pml);
     c->amax = reinterpret_cast<int32_t*>(b + o_amax);
+    c->am_best = reinterpret_cast<float*>(b + o_sb);
+    c->am_second = reinterpret_cast<float*>(b + o_s2);
+    c->am_idx = reinterpret_cast<int*>(b + o_si);
+    c->am_arrivals = reinterpret_cast<int*>(b + o_arr);
     *out = c;
     return CATS_OK;
 }

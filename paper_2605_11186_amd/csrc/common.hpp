@@ -202,7 +202,14 @@ struct ArgmaxArgs {
     float* logits;      // optional [T][V]
     int32_t* amax;      // [T]
     float* margin;      // optional [T]
+    // scratch of the slice merge: [T][ARGMAX_SLICES] each, and [T] arrival counters that are zero
+    // between launches
+    float* slice_best;
+    float* slice_second;
+    int* slice_idx;
+    int* arrivals;
 };
+constexpr int ARGMAX_SLICES = 16;
 void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
 
 // ---------------------------------------------------------------- attention

@@ -174,41 +174,76 @@ __global__ void cats_swiglu(SwigluArgs a) {
     *reinterpret_cast<uint2*>(a.h_lo + o) = lo;
 }
 
-// Per node: add up the logits partials, optionally store them, find the largest
-// (lowest index on ties) and the runner-up value.  One workgroup per node.
-constexpr int AM_THREADS = 1024;
+// Per node: add up the logits partials, optionally store them, find the largest (lowest index
+// on ties) and the runner-up value.  grid (T, AM_SLICES): every workgroup takes one slice of the
+// vocabulary (16-byte piece loads in batches when the row pitch allows, else one column at a
+// time), leaves its (best, index, runner-up) in scratch and the last workgroup of a node to
+// arrive merges the slices in slice order and resets the node's arrival counter.
+constexpr int AM_THREADS = 256;
+constexpr int AM_SLICES = ARGMAX_SLICES;
+
+__device__ __forceinline__ void top2_merge(float& b, int& bi, float& s2, float ob, int oi, float os) {
+    if (ob > b || (ob == b && oi < bi)) {
+        s2 = fmaxf(fmaxf(s2, os), b);
+        b = ob;
+        bi = oi;
+    } else {
+        s2 = fmaxf(s2, ob);
+    }
+}
+
 __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
     __shared__ float s_best[AM_THREADS / 64], s_second[AM_THREADS / 64];
     __shared__ int s_idx[AM_THREADS / 64];
-    const int t = blockIdx.x, tid = threadIdx.x;
+    const int t = blockIdx.x, slice = blockIdx.y, tid = threadIdx.x;
     float best = -INFINITY, second = -INFINITY;
     int bidx = 0x7fffffff;
     const float rs = row_scale(a.ns, t);
-    for (int v = tid; v < a.V; v += AM_THREADS) {
-        const float val = rs * sum_pieces(a.part, a.plan, a.T, a.ld, t, v);
-        if (a.logits) a.logits[static_cast<size_t>(t) * a.V + v] = val;
-        if (val > best) {  // indices ascend within a thread: strict > keeps the lowest
+    auto take = [&](float val, int v) {   // indices ascend within a thread: strict > keeps the lowest
+        if (val > best) {
             second = best;
             best = val;
             bidx = v;
         } else if (val > second) {
             second = val;
         }
-    }
-    auto merge = [](float& b, int& bi, float& s2, float ob, int oi, float os) {
-        if (ob > b || (ob == b && oi < bi)) {
-            s2 = fmaxf(fmaxf(s2, os), b);
-            b = ob;
-            bi = oi;
-        } else {
-            s2 = fmaxf(s2, ob);
-        }
     };
+    if (a.ld % 4 == 0) {
+        const int groups = (a.V + 3) / 4;
+        const int g_begin = static_cast<int>(static_cast<int64_t>(groups) * slice / AM_SLICES);
+        const int g_end = static_cast<int>(static_cast<int64_t>(groups) * (slice + 1) / AM_SLICES);
+        const size_t stride = static_cast<size_t>(a.T) * a.ld;
+        for (int g = g_begin + tid; g < g_end; g += AM_THREADS) {
+            const int v = 4 * g;   // the four columns share a tile (tile heights are multiples of 4)
+            f32x4 val = sum_pieces4(a.part + static_cast<size_t>(t) * a.ld + v, stride, plan_pieces(a.plan, v / a.plan.bn));
+            val *= rs;
+            if (a.logits) {
+                if (a.V % 4 == 0) {
+                    *reinterpret_cast<f32x4*>(a.logits + static_cast<size_t>(t) * a.V + v) = val;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (v + e < a.V) a.logits[static_cast<size_t>(t) * a.V + v + e] = val[e];
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (v + e < a.V) take(val[e], v + e);
+        }
+    } else {
+        const int v_begin = static_cast<int>(static_cast<int64_t>(a.V) * slice / AM_SLICES);
+        const int v_end = static_cast<int>(static_cast<int64_t>(a.V) * (slice + 1) / AM_SLICES);
+        for (int v = v_begin + tid; v < v_end; v += AM_THREADS) {
+            const float val = rs * sum_pieces(a.part, a.plan, a.T, a.ld, t, v);
+            if (a.logits) a.logits[static_cast<size_t>(t) * a.V + v] = val;
+            take(val, v);
+        }
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         const float ob = __shfl_xor(best, o), os = __shfl_xor(second, o);
         const int oi = __shfl_xor(bidx, o);
-        merge(best, bidx, second, ob, oi, os);
+        top2_merge(best, bidx, second, ob, oi, os);
     }
     if ((tid & 63) == 0) {
         s_best[tid >> 6] = best;
@@ -216,11 +251,32 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
         s_idx[tid >> 6] = bidx;
     }
     __syncthreads();
-    if (tid == 0) {
-        for (int w = 1; w < AM_THREADS / 64; ++w) merge(best, bidx, second, s_best[w], s_idx[w], s_second[w]);
-        a.amax[t] = bidx;
-        if (a.margin) a.margin[t] = best - second;
-    }
+    if (tid != 0) return;
+    for (int w = 1; w < AM_THREADS / 64; ++w) top2_merge(best, bidx, second, s_best[w], s_idx[w], s_second[w]);
+    // publish this slice; the last arriver of the node merges.  The slice results move with
+    // device-coherent (relaxed, device-scope) atomic stores and loads, which bypass the
+    // per-XCD caches; waiting for the stores' acknowledgement before the arrival count is
+    // raised orders them without a cache write-back / invalidate, which costs microseconds here.
+    float* pb = a.slice_best + static_cast<size_t>(t) * AM_SLICES;
+    float* ps = a.slice_second + static_cast<size_t>(t) * AM_SLICES;
+    int* pi = a.slice_idx + static_cast<size_t>(t) * AM_SLICES;
+    __hip_atomic_store(pb + slice, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(ps + slice, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(pi + slice, bidx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const int arrived = __hip_atomic_fetch_add(a.arrivals + t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::: "memory");
+    if (arrived != AM_SLICES - 1) return;
+    best = -INFINITY;
+    second = -INFINITY;
+    bidx = 0x7fffffff;
+    for (int sl = 0; sl < AM_SLICES; ++sl)
+        top2_merge(best, bidx, second, __hip_atomic_load(pb + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                   __hip_atomic_load(pi + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                   __hip_atomic_load(ps + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    a.amax[t] = bidx;
+    if (a.margin) a.margin[t] = best - second;
+    __hip_atomic_store(a.arrivals + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
 }  // namespace
@@ -246,5 +302,5 @@ void launch_swiglu(const SwigluArgs& a, hipStream_t st) {
 }
 
 void launch_argmax(const ArgmaxArgs& a, hipStream_t st) {
-    hipLaunchKernelGGL(cats_argmax, dim3(a.T), dim3(AM_THREADS), 0, st, a);
+    hipLaunchKernelGGL(cats_argmax, dim3(a.T, AM_SLICES), dim3(AM_THREADS), 0, st, a);
 }
