@@ -243,11 +243,11 @@ void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipS
                        src, dst, rows, cols, C, n_vec);
 }
 
-GemmPlan make_gemm_plan(int N, int K, int target_wgs) {
+GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn) {
     GemmPlan p;
-    p.bn = GEMM_BN;
+    p.bn = bn;
     p.chunks = (K + GEMM_KC - 1) / GEMM_KC;
-    const int tiles = (N + GEMM_BN - 1) / GEMM_BN;
+    const int tiles = (N + bn - 1) / bn;
     p.items = tiles * p.chunks;
     p.n_wgs = target_wgs < p.items ? target_wgs : p.items;
     return p;
@@ -266,21 +266,28 @@ int gemm_plan_max_pieces(const GemmPlan& p) {
 // With events given, they are attached to the dispatch itself (kernel begin / end
 // timestamps), so the elapsed time is the kernel's execution time without launch latency.
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    constexpr int NW = GEMM_BN / 32;
-    const dim3 grid(a.plan.n_wgs), block(64 * NW);
+    const int nw = a.plan.bn / 32;   // waves per workgroup: 8 (256-row tiles) or 4 (128-row tiles)
+    const dim3 grid(a.plan.n_wgs), block(64 * nw);
     const int tb = (a.T + 31) / 32;
-#define CATS_LAUNCH(TBV, STV)                                                                          \
+#define CATS_LAUNCH_NW(TBV, NWV, STV)                                                                  \
     if (a.packed)                                                                                      \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV, true>), grid, block, 0, st, ev_start, \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWV, STV, true>), grid, block, 0, st, ev_start, \
                               ev_stop, 0, a);                                                          \
     else                                                                                               \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NW, STV, false>), grid, block, 0, st, ev_start, \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWV, STV, false>), grid, block, 0, st, ev_start, \
                               ev_stop, 0, a)
+#define CATS_LAUNCH(TBV, STV)                \
+    if (nw == 4) {                           \
+        CATS_LAUNCH_NW(TBV, 4, STV);         \
+    } else {                                 \
+        CATS_LAUNCH_NW(TBV, 8, STV);         \
+    }
     switch (tb) {
-        case 1: CATS_LAUNCH(1, GEMM_ST); break;
-        case 2: CATS_LAUNCH(2, GEMM_ST); break;
-        case 3: CATS_LAUNCH(3, GEMM_ST4); break;
-        default: CATS_LAUNCH(4, GEMM_ST4); break;
+        case 1: CATS_LAUNCH(1, GEMM_ST) break;
+        case 2: CATS_LAUNCH(2, GEMM_ST) break;
+        case 3: CATS_LAUNCH(3, GEMM_ST4) break;
+        default: CATS_LAUNCH(4, GEMM_ST4) break;
     }
 #undef CATS_LAUNCH
+#undef CATS_LAUNCH_NW
 }
