@@ -40,6 +40,10 @@ WORKLOADS = {
     # first (chain, then corrections alone), the remaining layers on the whole tree from hidden states
     "7b_cascade_g5": dict(model="V7B", ctx=1024, tree="cascade", cascade=dict(gamma=5, l_sv=8, corr=(1, 3)),
                           label="7B-shape cascaded cycle: draft chain of 5 + 2 correction leaves (8 nodes); layers 0..7 on the chain, then on the corrections alone, layers 8..31 + LM head on the tree; KV context 1024"),
+    # stage 1 of the cascaded cycle: token-at-a-time drafting through the first layers and an attention-only
+    # adapter with the shared LM head (T = 1: the matrix-vector corner of the weight-streaming product)
+    "7b_draft_loop_g5": dict(model="V7B", ctx=1024, tree="cascade", draft=dict(gamma=5, l_dm=2),
+                             label="7B-shape draft loop: 5 tokens one at a time through layers 0..1, an attention-only adapter and the shared LM head; KV context 1024"),
     # adapter-training side kernel (Eq. 2): not a verify step, its own metric and roofline
     "reduced_kl_p4096_v32000_k10": dict(model="V7B", ctx=0, tree="binary15", loss=dict(P=4096, V=32000, K=10),
                                         label="Reduced KL loss + gradient, 4096 positions x vocab 32000, top-10, LM-like seeded logits"),
@@ -217,7 +221,10 @@ def main():
     dims = getattr(synth, wl["model"])
     S = args.ctx or wl["ctx"]
     cascade = wl.get("cascade")
-    if cascade:
+    draft = wl.get("draft")
+    if draft:
+        casc_tok, parent, depth, _ = cats.cats_build_tree(1, list(range(2, 2 + draft["gamma"])))
+    elif cascade:
         rng = np.random.default_rng(args.seed)
         drafts = rng.integers(0, dims.vocab, cascade["gamma"]).astype(np.int32)
         corrections = np.full(cascade["gamma"], -1, dtype=np.int32)
@@ -239,7 +246,7 @@ def main():
     iterate = wl.get("iterate", 0)
     offload = wl.get("offload", False)
     max_ctx = (S + T + (iterate * 9 if iterate else 0) + 63) // 64 * 64
-    tok = casc_tok if cascade else synth.distinct_sibling_tokens(parent, dims.vocab, seed)
+    tok = casc_tok if (cascade or draft) else synth.distinct_sibling_tokens(parent, dims.vocab, seed)
     golden = None
     gfile = ROOT / "tests" / "golden" / "config2_tree_7b.txt"
     if args.workload == "7b_t63_s1024" and seed == 11186 and not args.tree_nodes and not args.ctx and gfile.exists():
@@ -257,7 +264,8 @@ def main():
     d_layers = []
     n_keep = 0 if args.no_cpu_baseline else min(args.cpu_sample_layers, L)
     pinned_layers = []  # offload regime: the weights stay in pinned host memory
-    for l in range(L):
+    n_model_layers = draft["l_dm"] if draft else L
+    for l in range(n_model_layers):
         w = synth.layer_weights(dims, seed, l)
         dw = cats.pack_layer({k: to_dev(v) for k, v in w.items()})   # one-time re-tiling, row-major copy dropped
         if offload:
@@ -272,7 +280,7 @@ def main():
     d_final["w_lm"] = cats.cats_pack_matrix(d_final["w_lm"])
     d_embed = to_dev(embed)
     ks, vs, host_kv = [], [], []
-    for l in range(L):
+    for l in range(n_model_layers + (1 if draft else 0)):   # the draft adapter has a cache of its own
         k_rows, v_rows = synth.random_kv_context(dims, seed, l, S)
         k, v = cats.kv_from_rows(to_dev(k_rows), to_dev(v_rows), dims.n_heads, dims.head_dim, max_ctx)
         ks.append(k)
@@ -344,6 +352,53 @@ def main():
                           "config": {"workload": wl["label"], "key": args.workload, "layers": L, "seed": seed,
                                      "value_is": "fastest point of the sweep"},
                           "sweep": points}))
+        return
+
+    if draft:
+        g, l_dm = draft["gamma"], draft["l_dm"]
+        ad = synth.adapter_weights(dims, seed, 0)
+        d_ad = cats.pack_layer({k: to_dev(v) for k, v in ad.items() if k != "g_out"})
+        g_out = to_dev(ad["g_out"])
+        ad_arr = cats.layer_array([d_ad])
+        kv_model = cats.kv_array(ks[:l_dm], vs[:l_dm])
+        kv_ad = cats.kv_array(ks[l_dm:], vs[l_dm:])
+        h = torch.empty(1, dims.hidden, dtype=torch.float32, device=dev)
+        o = torch.empty(1, dims.hidden, dtype=torch.float32, device=dev)
+        amax = torch.empty(1, dtype=torch.int32, device=dev)
+        amax_host = torch.empty(1, dtype=torch.int32).pin_memory()
+
+        def draft_cycle():
+            toks = [1]
+            for k in range(g):
+                chain = cats.cats_build_tree(toks[0], toks[1:])
+                cats.cats_set_tree(ctx, *chain[:3], stream)
+                cats.cats_verify_nodes(ctx, layers_arr, 0, l_dm, d_embed, None, kv_model, S, k, h, stream)
+                cats.cats_verify_nodes(ctx, ad_arr, 0, 1, None, h, kv_ad, S, k, o, stream)
+                cats.cats_lm_head_argmax(ctx, o, g_out, d_final["w_lm"], amax, stream=stream)
+                amax_host.copy_(amax, non_blocking=True)
+                torch.cuda.synchronize()
+                toks.append(int(amax_host[0]))
+            return toks
+
+        for _ in range(args.warmup):
+            draft_cycle()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            toks = draft_cycle()
+        torch.cuda.synchronize()
+        ms_cycle = (time.perf_counter() - t1) / args.steps * 1e3
+        w_tok = (l_dm * dims.layer_weight_elems() + 4 * dims.hidden * dims.hidden + dims.vocab * dims.hidden) * 2
+        cats.cats_destroy(ctx)
+        print(json.dumps({"metric": "draft tokens/sec", "value": round(g / (ms_cycle * 1e-3), 1), "unit": "tokens/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(ms_cycle, 4), "higher_is_better": True, "scaling": "weak",
+                          "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": wl["label"], "key": args.workload, "gamma": g, "l_dm": l_dm,
+                                     "ctx_len": S, "seed": seed, "drafted": toks[1:]},
+                          "draft": {"us_per_token": round(ms_cycle * 1e3 / g, 1), "weight_bytes_per_token": w_tok,
+                                    "weight_gbs": round(w_tok * g / (ms_cycle * 1e-3) / 1e9, 1),
+                                    "note": "every token ends with a host read-back of the drafted id"}}))
         return
 
     if cascade:

@@ -64,7 +64,12 @@ typedef struct {
 
 /* One decoder layer, bf16.  wq/wk/wv/wo: [hidden][hidden]; w_gate/w_up:
  * [ffn][hidden]; w_down: [hidden][ffn]; g_attn/g_ffn: RMSNorm gains [hidden].
- * With packed_weights the seven matrices are cats_pack_matrix outputs instead. */
+ * With packed_weights the seven matrices are cats_pack_matrix outputs instead.
+ * An attention-only block (the draft and shallow-verifier adapters of Sec. 3.3: normalisation,
+ * one attention layer, residual; the second normalisation is the g_final of the LM-head call)
+ * has w_gate = w_up = w_down = g_ffn = NULL: x += attention(rmsnorm(x, g_attn)) and nothing
+ * else.  Either all four are NULL or none (CATS_EINVAL otherwise); the host-streamed entry
+ * point takes full layers only. */
 typedef struct {
     const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down, *g_attn, *g_ffn;
 } cats_layer_weights;
@@ -233,10 +238,15 @@ int cats_verify_tree_streamed(cats_ctx *ctx, const cats_layer_weights *host_laye
                               float *margin_out, cats_accept_result *out_dev,
                               cats_accept_result *out_host, void *stream);
 
-/* Final RMSNorm + LM head + argmax alone (Algorithm 1: p_tgt = softmax(H(H_tgt));
- * greedy acceptance needs only the argmax).  hidden: float32 [T][hidden]. */
-int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, const void *g_final, const void *w_lm,
-                        float *logits_out, int32_t *argmax_out, float *margin_out, void *stream);
+/* Final RMSNorm + LM head + argmax alone (Algorithm 1: p_tgt = softmax(H(H_tgt)) for the
+ * target, y = argmax H(o) behind the draft and shallow-verifier adapters, whose second
+ * normalisation gain is passed as g_final: the LM head is shared; greedy decisions need only the
+ * argmax).  hidden: DEVICE float32 [n_rows][hidden], 1 <= n_rows <= max_tree (any rows: the
+ * tree set in the context plays no part).  Outputs (DEVICE): argmax_out int32 [n_rows]; optional
+ * logits_out float32 [n_rows][vocab] and margin_out float32 [n_rows]. */
+int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, int32_t n_rows, const void *g_final,
+                        const void *w_lm, float *logits_out, int32_t *argmax_out, float *margin_out,
+                        void *stream);
 
 /* Measurement aid for the weight-streaming GEMM (the layer-weight pass of the
  * "Target verification pass"): while enabled, every GEMM launch made through

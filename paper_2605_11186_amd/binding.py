@@ -97,8 +97,8 @@ _SIGNATURES = {
     "cats_pack_matrix": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
-    "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                            C.c_void_p, C.c_void_p],
+    "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                            C.c_void_p, C.c_void_p, C.c_void_p],
 }
 
 
@@ -299,8 +299,9 @@ def cats_verify_tree_streamed(ctx, host_layers_arr, layer_begin: int, layer_end:
 
 def cats_lm_head_argmax(ctx, hidden, g_final, w_lm, argmax_out, logits_out=None, margin_out=None,
                         stream=None):
-    _check(library().cats_lm_head_argmax(ctx, _dp(hidden), _dp(g_final), _dp(w_lm), _dp(logits_out),
-                                         _dp(argmax_out), _dp(margin_out), _stream(stream)))
+    """Rows are taken from hidden's shape [n_rows][hidden]."""
+    _check(library().cats_lm_head_argmax(ctx, _dp(hidden), int(hidden.shape[0]), _dp(g_final), _dp(w_lm),
+                                         _dp(logits_out), _dp(argmax_out), _dp(margin_out), _stream(stream)))
 
 
 def cats_profile_gemm(ctx, enable: bool):
@@ -317,14 +318,18 @@ def cats_profile_gemm_read(ctx):
 # ---------------------------------------------------------------- marshalling helpers
 def layer_weights_struct(tensors: dict) -> LayerWeights:
     """Struct of device pointers from a dict name -> bf16 tensor (kept alive by the caller)."""
-    return LayerWeights(**{n: tensors[n].data_ptr() for n, _ in LayerWeights._fields_})
+    return LayerWeights(**{n: (tensors[n].data_ptr() if tensors.get(n) is not None else None)
+                           for n, _ in LayerWeights._fields_})
 
 
 def layer_array(layer_dicts):
+    """LayerWeights array from dicts name -> tensor; names that are missing or None stay NULL
+    (an attention-only block has no w_gate / w_up / w_down / g_ffn)."""
     arr = (LayerWeights * len(layer_dicts))()
     for i, t in enumerate(layer_dicts):
         for n, _ in LayerWeights._fields_:
-            setattr(arr[i], n, t[n].data_ptr())
+            if t.get(n) is not None:
+                setattr(arr[i], n, t[n].data_ptr())
     return arr
 
 

@@ -19,6 +19,7 @@ struct cats_ctx {
     int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
     int T;  // 0 = no tree set
     int n0 = 0;  // first node of the range being forwarded (0 except inside cats_verify_nodes)
+    int rows = 0;  // rows the row kernels and GEMMs of the call being enqueued work on (set by every entry point)
     // scratch
     float* x;        // [max_tree][H] residual stream
     // activations that feed a GEMM or the attention products: high and low bf16 parts
@@ -89,8 +90,13 @@ int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
     // aim at one wave per SIMD (1024 SIMDs; the kernel needs most of the register file):
     // heads * chunks * query groups * waves per workgroup
-    const int tq = (c->T - c->n0 + 31) / 32;
-    int chunks = std::max(1, 1024 / std::max(1, c->d.n_heads * tq * ATTN_WAVES));
+    const int tq = (c->rows + 31) / 32;
+    static const int wave_target = [] {
+        const char* e = std::getenv("CATS_ATTN_WAVES");
+        const int v = e ? std::atoi(e) : 0;
+        return v > 0 ? v : 1024;
+    }();
+    int chunks = std::max(1, wave_target / std::max(1, c->d.n_heads * tq * ATTN_WAVES));
     chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
     return (n_blocks + chunks - 1) / chunks;
 }
@@ -101,17 +107,25 @@ NormScale norm_scale(const cats_ctx* c) {
     return NormScale{c->ss, (c->d.hidden + SS_COLS - 1) / SS_COLS, c->d.hidden, c->d.rms_eps};
 }
 
-int check_ctx_len(const cats_ctx* c, int32_t ctx_len) {
+// Common checks of the entry points that work on the tree; on success the call's row range
+// defaults to the whole tree (cats_verify_nodes narrows it afterwards).
+int check_ctx_len(cats_ctx* c, int32_t ctx_len) {
     if (!c) return CATS_EINVAL;
     if (c->T < 1) return CATS_ESTATE;
     if (ctx_len < 0) return CATS_EINVAL;
     if (static_cast<int64_t>(ctx_len) + c->T > c->d.max_ctx) return CATS_ECAPACITY;
+    c->n0 = 0;
+    c->rows = c->T;
     return CATS_OK;
 }
 
+// A full decoder layer, or an attention-only block (the adapters: norm, attention, residual):
+// then the three feed-forward matrices and g_ffn are all NULL.
+bool has_ffn(const cats_layer_weights* w) { return w->w_gate != nullptr; }
 bool layer_ok(const cats_layer_weights* w) {
-    return w && w->wq && w->wk && w->wv && w->wo && w->w_gate && w->w_up && w->w_down && w->g_attn &&
-           w->g_ffn;
+    if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_attn) return false;
+    if (w->w_gate || w->w_up || w->w_down || w->g_ffn) return w->w_gate && w->w_up && w->w_down && w->g_ffn;
+    return true;
 }
 
 int seg_pad_of(const cats_ctx* c, int seg_rows) {
@@ -133,7 +147,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.packed = c->d.packed_weights;
     g.N = n_seg * g.seg_pad;
     g.K = K;
-    g.T = c->T - c->n0;
+    g.T = c->rows;
     g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn());
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
@@ -156,7 +170,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.anc = c->anc;
     a.T = c->T;
-    a.Tq = c->T - c->n0;
+    a.Tq = c->rows;
     a.q0 = c->n0;
     a.H = c->d.hidden;
     a.nh = c->d.n_heads;
@@ -178,7 +192,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
 // exit x is updated and, if next_gain is given, c->xn holds rmsnorm(x)*next_gain.
 void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cats_kv_layer* kv,
                    int ctx_len, const void* next_gain, hipStream_t st) {
-    const int H = c->d.hidden, F = c->d.ffn, T = c->T - c->n0;   // rows = nodes n0 .. T-1
+    const int H = c->d.hidden, F = c->d.ffn, T = c->rows;   // nodes n0 .. n0 + rows - 1
     // attention block
     GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, 3, H, H, st);
     QkvRopeArgs qa;
@@ -206,7 +220,7 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     rn.token = nullptr;
     rn.part = c->part;
     rn.plan = plan;
-    rn.gain = static_cast<const bf16_t*>(w->g_ffn);
+    rn.gain = static_cast<const bf16_t*>(has_ffn(w) ? w->g_ffn : next_gain);
     rn.xn = c->xn;
     rn.xn_lo = c->xn_lo;
     rn.ss = c->ss;
@@ -214,6 +228,7 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     rn.H = H;
     rn.eps = c->d.rms_eps;
     launch_residual_norm(rn, st);
+    if (!has_ffn(w)) return;   // attention-only block
     // feed-forward block
     plan = enqueue_gemm(c, c->xn, c->xn_lo, w->w_gate, w->w_up, nullptr, 2, F, H, st);
     SwigluArgs sa;
@@ -250,7 +265,7 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
     am.part = c->part;
     am.plan = plan;
     am.ns = norm_scale(c);
-    am.T = c->T;
+    am.T = c->rows;
     am.V = c->d.vocab;
     am.ld = seg_pad_of(c, c->d.vocab);
     am.logits = logits_out;
@@ -486,11 +501,14 @@ int cats_accept_and_compact(cats_ctx* ctx, const int32_t* node_argmax, const cat
                                   as_stream(stream));
 }
 
-int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final, const void* w_lm,
-                        float* logits_out, int32_t* argmax_out, float* margin_out, void* stream) {
+int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, int32_t n_rows, const void* g_final,
+                        const void* w_lm, float* logits_out, int32_t* argmax_out, float* margin_out,
+                        void* stream) {
     if (!ctx) return CATS_EINVAL;
-    if (ctx->T < 1) return CATS_ESTATE;
     if (!hidden || !g_final || !w_lm || !argmax_out) return CATS_EINVAL;
+    if (n_rows < 1 || n_rows > ctx->d.max_tree) return CATS_EINVAL;
+    ctx->n0 = 0;
+    ctx->rows = n_rows;
     hipStream_t st = as_stream(stream);
     ResidualNormArgs rn;
     rn.x = const_cast<float*>(hidden);  // read only: no source/partials given, so nothing is written back
@@ -503,7 +521,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, const void* g_final,
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
     rn.ss = ctx->ss;
-    rn.T = ctx->T;
+    rn.T = ctx->rows;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
     launch_residual_norm(rn, st);
@@ -530,7 +548,7 @@ static void enqueue_rows_and_layers(cats_ctx* ctx, const cats_layer_weights* lay
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
     rn.ss = ctx->ss;
-    rn.T = ctx->T - ctx->n0;
+    rn.T = ctx->rows;
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
     launch_residual_norm(rn, st);
@@ -581,10 +599,10 @@ int cats_verify_nodes(cats_ctx* ctx, const cats_layer_weights* layers, int32_t l
     if ((embed == nullptr) == (hidden_in == nullptr)) return CATS_EINVAL;
     if (node_begin < 0 || node_begin >= ctx->T || !hidden_out) return CATS_EINVAL;
     hipStream_t st = as_stream(stream);
-    ctx->n0 = node_begin;   // read by the enqueue helpers; reset before returning
+    ctx->n0 = node_begin;   // read by the enqueue helpers
+    ctx->rows = ctx->T - node_begin;
     enqueue_rows_and_layers(ctx, layers, layer_begin, layer_end, embed, hidden_in, nullptr, kv, ctx_len, st);
     const size_t bytes = sizeof(float) * static_cast<size_t>(ctx->T - node_begin) * ctx->d.hidden;
-    ctx->n0 = 0;
     HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, bytes, hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipGetLastError());
     return CATS_OK;
@@ -691,7 +709,7 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
         !kv_ok(kv, layer_begin, layer_end))
         return CATS_EINVAL;
     for (int l = layer_begin; l < layer_end; ++l)
-        if (!layer_ok(&host_layers[l])) return CATS_EINVAL;
+        if (!layer_ok(&host_layers[l]) || !has_ffn(&host_layers[l])) return CATS_EINVAL;
     if (!ctx->copy_stream) {  // created on first use, at the default priority
         HIP_TRY(hipStreamCreateWithFlags(&ctx->copy_stream, hipStreamNonBlocking));
         for (int i = 0; i < 2; ++i) {

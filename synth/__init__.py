@@ -8,7 +8,7 @@ the seeded logit rows of the distillation-loss kernel.
 """
 from .model import (ModelDims, TINY, V7B, V13B, bf16_bits_from_f32,
                     f32_from_bf16_bits, normal_bf16, layer_weights,
-                    final_weights, embedding, random_kv_context,
+                    final_weights, adapter_weights, embedding, random_kv_context,
                     context_tokens, random_hidden, MATRIX_IDS)
 from .trees import (chain_tree, complete_binary_tree, random_tree,
                     product_tree_pruned, chain_with_corrections,

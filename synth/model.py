@@ -115,6 +115,19 @@ def layer_weights(dims: ModelDims, seed: int, layer: int) -> dict:
     return w
 
 
+def adapter_weights(dims: ModelDims, seed: int, which: int) -> dict:
+    """An attention-only adapter block (draft adapter which=0, shallow-verifier adapter which=1):
+    the four attention matrices, the gain of the normalisation in front of the attention
+    (g_attn) and the gain of the normalisation in front of the shared LM head (g_out).  Drawn
+    like a decoder layer's, under layer ids no model reaches."""
+    h = dims.hidden
+    layer = 100000 + which
+    w = {name: normal_bf16((seed, layer, MATRIX_IDS[name]), (h, h), 0.02) for name in ("wq", "wk", "wv", "wo")}
+    w["g_attn"] = normal_bf16((seed, layer, MATRIX_IDS["g_attn"]), (h,), 0.02, 1.0)
+    w["g_out"] = normal_bf16((seed, layer, MATRIX_IDS["g_final"]), (h,), 0.02, 1.0)
+    return w
+
+
 def final_weights(dims: ModelDims, seed: int) -> dict:
     """Final norm gain and the (untied) LM head [vocab][hidden]."""
     return {

@@ -139,3 +139,145 @@ def test_verify_nodes_rejects_bad_ranges(tiny4):
     with pytest.raises(cats.CatsError) as e:
         cats.cats_verify_nodes(p.ctx, p.layers_arr, 0, 1, p.d_embed, None, kv_arr, 320, 0, out)
     assert e.value.status == cats.CATS_ECAPACITY
+
+
+# ---------------------------------------------------------------------------------------------
+# One whole cascaded cycle (Alg. 1, stages 1-3) with synthetic adapters.
+#
+# The adapters (Sec. 3.3: normalisation, one attention layer, residual, normalisation, shared LM
+# head) are attention-only blocks with their own KV caches.  On the oracle side an adapter is a
+# decoder layer whose feed-forward matrices are zero (x += 0), appended to the target's layer
+# list, so the oracle needs no code of its own for it; its second normalisation is the final
+# gain of the LM-head call.
+def zero_ffn_layer(dims, adapter):
+    z = lambda r, c: np.zeros((r, c), dtype=np.uint16)
+    return {"wq": adapter["wq"], "wk": adapter["wk"], "wv": adapter["wv"], "wo": adapter["wo"],
+            "g_attn": adapter["g_attn"], "g_ffn": adapter["g_attn"],
+            "w_gate": z(dims.ffn, dims.hidden), "w_up": z(dims.ffn, dims.hidden), "w_down": z(dims.hidden, dims.ffn)}
+
+
+def test_whole_cycle_with_synthetic_adapters(tiny4):
+    import dataclasses
+    from oracle.cats_oracle import Oracle
+    from gpu_common import to_dev_bf16
+    p = tiny4
+    d = p.dims
+    L, L_DM, L_SV, gamma, S = p.L, 1, 2, 4, 61
+    seed = 4321
+    ad = [synth.adapter_weights(d, seed, w) for w in (0, 1)]          # draft, shallow verifier
+    # ---- oracle: target layers 0..3, then the two adapters as layers 4 and 5
+    dims6 = dataclasses.replace(d, n_layers=L + 2)
+    layers6 = p.layers + [zero_ffn_layer(d, a) for a in ad]
+    orc = [Oracle(dims6, layers6, {"g_final": g, "w_lm": p.final["w_lm"]}, p.embed)
+           for g in (ad[0]["g_out"], ad[1]["g_out"], p.final["g_final"])]   # LM head behind each norm
+    kc, vc = orc[0].new_cache(p.max_ctx)
+    for l in range(L + 2):
+        k, v = synth.random_kv_context(d, seed, l, S)
+        kc[l, :S], vc[l, :S] = synth.f32_from_bf16_bits(k), synth.f32_from_bf16_bits(v)
+    # ---- device: the same caches, adapters as attention-only blocks
+    saved_L = p.L
+    p.L = L + 2
+    ks, vs = p.device_cache_from_oracle(kc, vc, S)
+    p.L = saved_L
+    d_ad = [cats.pack_layer({k: to_dev_bf16(v) for k, v in a.items() if k != "g_out"}) for a in ad]
+    d_gout = [to_dev_bf16(a["g_out"]) for a in ad]
+    kv_target = cats.kv_array(ks[:L], vs[:L])
+    ad_arr = [cats.layer_array([w]) for w in d_ad]
+    ad_kv = [cats.kv_array(ks[L + i:L + i + 1], vs[L + i:L + i + 1]) for i in range(2)]
+    H = d.hidden
+    root = 77
+
+    def next_token_gpu(hidden_row, g_out):
+        amax = torch.empty(hidden_row.shape[0], dtype=torch.int32, device="cuda")
+        margin = torch.empty(hidden_row.shape[0], dtype=torch.float32, device="cuda")
+        cats.cats_lm_head_argmax(p.ctx, hidden_row, g_out, p.d_final["w_lm"], amax, margin_out=margin)
+        torch.cuda.synchronize()
+        return amax.cpu().numpy(), margin.cpu().numpy()
+
+    # ---- stage 1: draft loop, one token at a time (chain grows, only the new node is forwarded)
+    g_tokens, o_tokens = [root], [root]
+    h_dm = torch.zeros(gamma + 1, H, dtype=torch.float32, device="cuda")
+    o_hdm = np.zeros((gamma + 1, H))
+    kc_o, vc_o = kc.copy(), vc.copy()
+    for k in range(gamma + 1):
+        chain = cats.cats_build_tree(root, g_tokens[1:])
+        cats.cats_set_tree(p.ctx, *chain[:3])
+        cats.cats_verify_nodes(p.ctx, p.layers_arr, 0, L_DM, p.d_embed, None, kv_target, S, k, h_dm[k:k + 1])
+        o_hdm[k] = orc[0].causal_decode(kc_o, vc_o, S + k, tokens=[o_tokens[-1]], layer_end=L_DM)[0]
+        if k == gamma:
+            break   # the last draft token only needs its hidden state (it is a node of the tree)
+        out = torch.empty(1, H, dtype=torch.float32, device="cuda")
+        cats.cats_verify_nodes(p.ctx, ad_arr[0], 0, 1, None, h_dm[k:k + 1], ad_kv[0], S, k, out)
+        tok, _ = next_token_gpu(out, d_gout[0])
+        o_out = orc[0].causal_decode(kc_o, vc_o, S + k, hidden_in=o_hdm[k:k + 1], layer_begin=L, layer_end=L + 1)
+        o_amax, o_margin = orc[0].argmax_margin(orc[0].lm_head(o_out))
+        assert o_margin[0] > MARGIN, "pick another seed: near-tie in the draft stream"
+        assert rel_err(out.cpu().numpy(), o_out) <= REL_TOL
+        g_tokens.append(int(tok[0]))
+        o_tokens.append(int(o_amax[0]))
+    assert g_tokens == o_tokens
+    assert rel_err(h_dm.cpu().numpy(), o_hdm) <= REL_TOL
+    drafts = np.array(g_tokens[1:], dtype=np.int32)
+
+    # ---- stage 2: shallow layers on all chain positions in parallel, verifier adapter, corrections
+    chain = cats.cats_build_tree(root, drafts)
+    cats.cats_set_tree(p.ctx, *chain[:3])
+    h_sv = torch.zeros(gamma + 1, H, dtype=torch.float32, device="cuda")
+    cats.cats_verify_nodes(p.ctx, p.layers_arr, L_DM, L_SV, None, h_dm, kv_target, S, 0, h_sv)
+    o_sv_out = torch.empty(gamma + 1, H, dtype=torch.float32, device="cuda")
+    cats.cats_verify_nodes(p.ctx, ad_arr[1], 0, 1, None, h_sv, ad_kv[1], S, 0, o_sv_out)
+    c_hat, _ = next_token_gpu(o_sv_out, d_gout[1])
+    o_hsv = orc[1].tree_forward(kc_o, vc_o, S, chain[1], chain[2], hidden_in=o_hdm, layer_begin=L_DM, layer_end=L_SV)
+    o_svo = orc[1].tree_forward(kc_o, vc_o, S, chain[1], chain[2], hidden_in=o_hsv, layer_begin=L + 1, layer_end=L + 2)
+    o_chat, o_cm = orc[1].argmax_margin(orc[1].lm_head(o_svo))
+    assert rel_err(h_sv.cpu().numpy(), o_hsv) <= REL_TOL and rel_err(o_sv_out.cpu().numpy(), o_svo) <= REL_TOL
+    assert (o_cm[:gamma] > MARGIN).all(), "pick another seed: near-tie in the verifier's tokens"
+    assert np.array_equal(c_hat[:gamma], o_chat[:gamma])
+    corrections = c_hat[:gamma].astype(np.int32)       # position i judges draft i; equal tokens add no branch
+    token, parent, depth, corr_node = cats.cats_build_tree(root, drafts, corrections)
+    T = len(parent)
+    assert T > gamma + 1, "untrained adapters disagree: there must be correction branches"
+
+    # ---- corrections alone through the draft and shallow layers, then stage 3 on the whole tree
+    cats.cats_set_tree(p.ctx, token, parent, depth)
+    h_all = torch.zeros(T, H, dtype=torch.float32, device="cuda")
+    h_all[: gamma + 1] = h_sv
+    cats.cats_verify_nodes(p.ctx, p.layers_arr, 0, L_SV, p.d_embed, None, kv_target, S, gamma + 1, h_all[gamma + 1:])
+    hidden = torch.empty(T, H, dtype=torch.float32, device="cuda")
+    logits = torch.empty(T, d.vocab, dtype=torch.float32, device="cuda")
+    amax = torch.empty(T, dtype=torch.int32, device="cuda")
+    host = cats.AcceptResult()
+    cats.cats_verify_tree(p.ctx, p.layers_arr, L_SV, L, None, h_all, p.d_final["g_final"], p.d_final["w_lm"],
+                          kv_target, S, p.res_dev, hidden_out=hidden, logits_out=logits, argmax_out=amax,
+                          out_host=host)
+    cats.cats_accept_and_compact(p.ctx, amax, kv_target, 0, L_SV, S, p.res_dev)
+    torch.cuda.synchronize()
+    g_acc = host.as_dict()
+    # oracle: the whole tree through the whole target in one pass (fresh target caches)
+    o_hidden = orc[2].tree_forward(kc, vc, S, parent, depth, tokens=token, layer_end=L)
+    o_logits = orc[2].lm_head(o_hidden)
+    o_amax, o_margin = orc[2].argmax_margin(o_logits)
+    assert rel_err(hidden.cpu().numpy(), o_hidden) <= REL_TOL and rel_err(logits.cpu().numpy(), o_logits) <= REL_TOL
+    safe = o_margin > MARGIN
+    assert np.array_equal(amax.cpu().numpy()[safe], o_amax[safe])
+    assert g_acc == orc[2].accept(token, parent, depth, amax.cpu().numpy(), S)
+    if safe.all():
+        assert g_acc == orc[2].accept(token, parent, depth, o_amax, S)
+    orc[2].compact(kc, vc, S, g_acc["path"])
+    for l in range(L):
+        gk, gv = p.device_rows(ks, vs, l, g_acc["new_ctx_len"])
+        assert rel_err(gk, kc[l, :g_acc["new_ctx_len"]]) <= REL_TOL
+        assert rel_err(gv, vc[l, :g_acc["new_ctx_len"]]) <= REL_TOL
+
+
+def test_attention_only_block_argument_rules(tiny4):
+    p = tiny4
+    ks, vs = p.device_cache_from_oracle(*p.oracle_cache_random(1, 8), 8)
+    kv_arr = cats.kv_array(ks, vs)
+    cats.cats_set_tree(p.ctx, *cats.cats_build_tree(1, [2, 3])[:3])
+    out = torch.empty(3, p.dims.hidden, dtype=torch.float32, device="cuda")
+    half = dict(p.d_layers[0])
+    half["w_up"] = None                               # some but not all feed-forward arrays
+    with pytest.raises(cats.CatsError) as e:
+        cats.cats_verify_nodes(p.ctx, cats.layer_array([half]), 0, 1, p.d_embed, None, kv_arr, 8, 0, out)
+    assert e.value.status == cats.CATS_EINVAL
