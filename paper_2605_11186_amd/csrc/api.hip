@@ -75,15 +75,20 @@ int target_wgs() {
 }
 
 // Weight rows per GEMM tile.  256-row tiles halve the re-reads of X, 128-row tiles halve the
-// number of partial tiles.  Measured back to back on one device (7B shapes, T = 63): 128 rows
-// for every product 5.10 ms per step, for the O projection only 5.155 ms, 256 rows everywhere
-// 5.09 ms.  256 it is; CATS_GEMM_BN = 128 selects the other variant for experiments.
-int gemm_bn() {
+// number of partial tiles.  Measured back to back on one device (7B shapes): at T = 63, 128
+// rows for every product 5.10 ms per step, for the O projection only 5.155 ms, 256 rows
+// everywhere 5.09 ms; at T = 96 6.40 vs 6.24 ms.  With more than 96 rows the 512-thread
+// variant runs out of registers (four accumulator blocks; 380 bytes of scratch per lane) while
+// a 256-thread workgroup may use the whole register file: T = 128 takes 7.86 ms with 128-row
+// tiles against 8.37 ms.  CATS_GEMM_BN (128 or 256) overrides the choice.
+int gemm_bn(int rows) {
     static const int forced = [] {
         const char* e = std::getenv("CATS_GEMM_BN");
-        return (e && std::atoi(e) == 128) ? 128 : 256;
+        const int v = e ? std::atoi(e) : 0;
+        return (v == 128 || v == 256) ? v : 0;
     }();
-    return forced;
+    if (forced) return forced;
+    return rows > 96 ? 128 : 256;
 }
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
@@ -148,7 +153,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.N = n_seg * g.seg_pad;
     g.K = K;
     g.T = c->rows;
-    g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn());
+    g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn(g.T));
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
