@@ -167,6 +167,33 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
                      float *margin_out, cats_accept_result *out_dev, cats_accept_result *out_host,
                      void *stream);
 
+/* Acceptance criterion Acc of the walk in cats_verify_tree / cats_verify_tree_streamed (Alg. 1:
+ * "greedy or typical"; Sec. 3.2 names typical acceptance by citation only, so the inequality is
+ * the cited work's: a candidate token x judged at its parent's distribution
+ * p = softmax(logits / temperature) passes when p(x) > min(epsilon, delta * exp(-H(p))), H the
+ * entropy of p).  mode 0 = greedy (the default: the token must equal the parent's argmax), mode
+ * 1 = typical with epsilon >= 0, delta >= 0, temperature > 0.  Everything else of the walk is
+ * unchanged: deepest accepted node, lowest index among equals, bonus token = argmax at that
+ * node.  cats_accept_and_compact always walks greedily from the argmax array it is given.
+ * HOST call, takes effect for later enqueues.  CATS_EINVAL for a bad mode or parameters. */
+int cats_set_acceptance(cats_ctx *ctx, int32_t mode, float epsilon, float delta, float temperature);
+
+/* Diagnostics of the last typical-mode cats_verify_tree on this context (copies enqueued on
+ * `stream`, which must be the stream of that call or ordered after it).  All optional, DEVICE
+ * float32 [T]: lse_out, entropy_out = log-sum-exp and entropy of softmax(logits / temperature)
+ * per node; prob_out, threshold_out = probability of each node's token under its parent's
+ * distribution and the threshold it was compared with (node 0: 1 and 0). */
+int cats_typical_stats(cats_ctx *ctx, float *lse_out, float *entropy_out, float *prob_out,
+                       float *threshold_out, void *stream);
+
+/* KV roll-back alone along an accept result that already exists on the device (Alg. 1: "Roll
+ * back KV ... along the accepted path"): rows ctx_len + path[k] -> ctx_len + k, k = 0..n_accepted,
+ * in layers [layer_begin, layer_end) of kv (HOST array indexed by layer).  For caches that the
+ * call which produced result_dev did not cover: the shallow layers of a staged cycle, adapter
+ * caches. */
+int cats_compact_along(cats_ctx *ctx, const cats_accept_result *result_dev, const cats_kv_layer *kv,
+                       int32_t layer_begin, int32_t layer_end, int32_t ctx_len, void *stream);
+
 /* Shallow-verification stage, correction re-forward (Sec. 3.2 "shallow verification"; Alg. 1,
  * stage 2: the correction tokens are forwarded again through the resident layers under the tree
  * mask while the main draft chain is not).  Forwards only nodes [node_begin, T) of the tree set

@@ -14,8 +14,8 @@ import numpy as np
 __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWeights", "KVLayer",
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
-           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_reduced_kl_loss",
-           "CATS_LOSS_MAX_K", "CATS_LOSS_MAX_VOCAB",
+           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_reduced_kl_loss", "cats_set_acceptance",
+           "cats_typical_stats", "cats_compact_along", "CATS_LOSS_MAX_K", "CATS_LOSS_MAX_VOCAB",
            "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
            "cats_verify_tree_streamed", "cats_layer_weight_bytes", "cats_packed_matrix_bytes",
@@ -94,6 +94,9 @@ _SIGNATURES = {
                         C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_reduced_kl_loss": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_set_acceptance": [C.c_void_p, C.c_int32, C.c_float, C.c_float, C.c_float],
+    "cats_typical_stats": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_compact_along": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p],
     "cats_pack_matrix": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p],
     "cats_profile_gemm": [C.c_void_p, C.c_int],
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
@@ -244,6 +247,20 @@ def cats_build_tree(root_token: int, main_tokens, corrections=None, capacity: in
         None if corr is None else corr.ctypes.data, int(capacity), token.ctypes.data, parent.ctypes.data,
         depth.ctypes.data, C.byref(n), corr_node.ctypes.data))
     return token[: n.value].copy(), parent[: n.value].copy(), depth[: n.value].copy(), corr_node[:gamma].copy()
+
+
+def cats_set_acceptance(ctx, mode: int, epsilon: float = 0.09, delta: float = 0.3, temperature: float = 1.0):
+    _check(library().cats_set_acceptance(ctx, int(mode), float(epsilon), float(delta), float(temperature)))
+
+
+def cats_typical_stats(ctx, lse_out=None, entropy_out=None, prob_out=None, threshold_out=None, stream=None):
+    _check(library().cats_typical_stats(ctx, _dp(lse_out), _dp(entropy_out), _dp(prob_out),
+                                        _dp(threshold_out), _stream(stream)))
+
+
+def cats_compact_along(ctx, result_dev, kv_arr, layer_begin: int, layer_end: int, ctx_len: int, stream=None):
+    _check(library().cats_compact_along(ctx, _dp(result_dev), kv_arr, int(layer_begin), int(layer_end),
+                                        int(ctx_len), _stream(stream)))
 
 
 def cats_reduced_kl_loss(target_logits, draft_logits, top_k: int, loss_out, per_pos_out, mask=None,

@@ -19,9 +19,12 @@ __global__ void cats_tree_upload(TreeUploadArgs a, int n, int32_t* token, int32_
 // token the target predicts at that node's parent.  The committed path ends at
 // the deepest accepted node, lowest index first among equals.  One workgroup of
 // CATS_MAX_TREE threads.
+// edge_ok (optional): per node, 1 when the node's token passes the acceptance criterion at its
+// parent; absent = greedy, the token must equal the parent's argmax.
 __global__ __launch_bounds__(CATS_MAX_TREE) void cats_accept(const int32_t* token, const int32_t* parent,
-                                                           const int32_t* depth, const int32_t* amax, int T,
-                                                           int ctx_len, cats_accept_result* out) {
+                                                           const int32_t* depth, const int32_t* amax,
+                                                           const uint8_t* edge_ok, int T, int ctx_len,
+                                                           cats_accept_result* out) {
     __shared__ int32_t s_tok[CATS_MAX_TREE], s_par[CATS_MAX_TREE], s_dep[CATS_MAX_TREE], s_amax[CATS_MAX_TREE];
     __shared__ int s_key[CATS_MAX_TREE];
     const int i = threadIdx.x;
@@ -38,7 +41,7 @@ __global__ __launch_bounds__(CATS_MAX_TREE) void cats_accept(const int32_t* toke
         int node = i;
         for (int step = 0; step < CATS_MAX_DEPTH && node > 0; ++step) {
             const int p = s_par[node];
-            ok = ok && (s_tok[node] == s_amax[p]);
+            ok = ok && (edge_ok ? edge_ok[node] != 0 : s_tok[node] == s_amax[p]);
             node = p;
         }
         if (ok) key = s_dep[i] * CATS_MAX_TREE + (CATS_MAX_TREE - 1 - i);
@@ -65,6 +68,28 @@ __global__ __launch_bounds__(CATS_MAX_TREE) void cats_accept(const int32_t* toke
         out->bonus_token = s_amax[best];
         out->new_ctx_len = ctx_len + n + 1;
     }
+}
+
+// Typical acceptance (the criterion the paper cites for Acc = typical): node j passes when the
+// probability of its token under its parent's distribution p = softmax(logits / temperature)
+// exceeds min(epsilon, delta * exp(-H(p))).  The parent's log-sum-exp and entropy come from the
+// LM-head epilogue; the one logit needed per node is added up from the GEMM's partial tiles.
+__global__ __launch_bounds__(CATS_MAX_TREE) void cats_typical_edges(TypicalArgs a) {
+    const int j = threadIdx.x;
+    if (j >= a.T) return;
+    if (j == 0) {
+        a.edge_ok[0] = 1;
+        a.prob[0] = 1.f;
+        a.thr[0] = 0.f;
+        return;
+    }
+    const int p = a.parent[j];
+    const float logit = row_scale(a.ns, p) * sum_pieces(a.part, a.plan, a.T, a.ld, p, a.token[j]);
+    const float prob = expf(logit * a.inv_temp - a.lse[p]);
+    const float thr = fminf(a.epsilon, a.delta * expf(-a.entropy[p]));
+    a.prob[j] = prob;
+    a.thr[j] = thr;
+    a.edge_ok[j] = prob > thr ? 1 : 0;
 }
 
 // Row ctx_len + path[k] -> row ctx_len + k for k = 0..n_accepted.  grid
@@ -105,9 +130,14 @@ void launch_tree_upload(const TreeUploadArgs& a, int n, int32_t* token, int32_t*
 }
 
 void launch_accept(const int32_t* token, const int32_t* parent, const int32_t* depth,
-                   const int32_t* amax, int T, int ctx_len, cats_accept_result* out, hipStream_t st) {
-    hipLaunchKernelGGL(cats_accept, dim3(1), dim3(CATS_MAX_TREE), 0, st, token, parent, depth, amax, T,
+                   const int32_t* amax, const uint8_t* edge_ok, int T, int ctx_len, cats_accept_result* out,
+                   hipStream_t st) {
+    hipLaunchKernelGGL(cats_accept, dim3(1), dim3(CATS_MAX_TREE), 0, st, token, parent, depth, amax, edge_ok, T,
                        ctx_len, out);
+}
+
+void launch_typical_edges(const TypicalArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(cats_typical_edges, dim3(1), dim3(CATS_MAX_TREE), 0, st, a);
 }
 
 void launch_compact(const CompactArgs& a, hipStream_t st) {

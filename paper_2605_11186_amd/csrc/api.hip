@@ -19,6 +19,11 @@ struct cats_ctx {
     int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
     int T;  // 0 = no tree set
     int n0 = 0;  // first node of the range being forwarded (0 except inside cats_verify_nodes)
+    // acceptance criterion of cats_verify_tree[_streamed]: 0 greedy, 1 typical
+    int accept_mode = 0;
+    float typ_epsilon = 0.09f, typ_delta = 0.3f, typ_inv_temp = 1.f;
+    float *typ_lse = nullptr, *typ_entropy = nullptr, *typ_slice = nullptr, *typ_prob = nullptr, *typ_thr = nullptr;
+    uint8_t* typ_edge = nullptr;
     int rows = 0;  // rows the row kernels and GEMMs of the call being enqueued work on (set by every entry point)
     // scratch
     float* x;        // [max_tree][H] residual stream
@@ -263,8 +268,10 @@ void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
     launch_rope_table(r, st);
 }
 
+// typical: also the per-node log-sum-exp / entropy and, per node, whether its token passes the
+// typical criterion at its parent (needs the whole tree as rows)
 void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
-                     float* margin_out, hipStream_t st) {
+                     float* margin_out, hipStream_t st, bool typical = false) {
     const GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
     ArgmaxArgs am;
     am.part = c->part;
@@ -280,27 +287,55 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
     am.slice_idx = c->am_idx;
     am.arrivals = c->am_arrivals;
     am.margin = margin_out;
+    am.inv_temp = c->typ_inv_temp;
+    am.lse = typical ? c->typ_lse : nullptr;
+    am.entropy = c->typ_entropy;
+    am.slice_stat = c->typ_slice;
     launch_argmax(am, st);
+    if (typical) {
+        TypicalArgs ta;
+        ta.token = c->token;
+        ta.parent = c->parent;
+        ta.part = c->part;
+        ta.plan = plan;
+        ta.ns = am.ns;
+        ta.T = c->T;
+        ta.ld = am.ld;
+        ta.lse = c->typ_lse;
+        ta.entropy = c->typ_entropy;
+        ta.inv_temp = c->typ_inv_temp;
+        ta.epsilon = c->typ_epsilon;
+        ta.delta = c->typ_delta;
+        ta.edge_ok = c->typ_edge;
+        ta.prob = c->typ_prob;
+        ta.thr = c->typ_thr;
+        launch_typical_edges(ta, st);
+    }
+}
+
+void enqueue_compact(cats_ctx* c, const cats_kv_layer* kv, int layer_begin, int layer_end, int ctx_len,
+                     const cats_accept_result* res_dev, hipStream_t st) {
+    if (layer_end <= layer_begin) return;
+    CompactArgs ca;
+    ca.n_layers = layer_end - layer_begin;
+    for (int l = layer_begin; l < layer_end; ++l) {
+        ca.k[l - layer_begin] = static_cast<bf16_t*>(kv[l].k);
+        ca.v[l - layer_begin] = static_cast<bf16_t*>(kv[l].v);
+    }
+    ca.nh = c->d.n_heads;
+    ca.d = c->d.head_dim;
+    ca.max_ctx = c->d.max_ctx;
+    ca.ctx_len = ctx_len;
+    ca.res = res_dev;
+    launch_compact(ca, st);
 }
 
 int enqueue_accept_compact(cats_ctx* c, const int32_t* amax, const cats_kv_layer* kv, int layer_begin,
                            int layer_end, int ctx_len, cats_accept_result* out_dev,
-                           cats_accept_result* out_host, hipStream_t st) {
-    launch_accept(c->token, c->parent, c->depth, amax, c->T, ctx_len, out_dev, st);
-    if (layer_end > layer_begin) {
-        CompactArgs ca;
-        ca.n_layers = layer_end - layer_begin;
-        for (int l = layer_begin; l < layer_end; ++l) {
-            ca.k[l - layer_begin] = static_cast<bf16_t*>(kv[l].k);
-            ca.v[l - layer_begin] = static_cast<bf16_t*>(kv[l].v);
-        }
-        ca.nh = c->d.n_heads;
-        ca.d = c->d.head_dim;
-        ca.max_ctx = c->d.max_ctx;
-        ca.ctx_len = ctx_len;
-        ca.res = out_dev;
-        launch_compact(ca, st);
-    }
+                           cats_accept_result* out_host, hipStream_t st, bool typical = false) {
+    launch_accept(c->token, c->parent, c->depth, amax, typical ? c->typ_edge : nullptr, c->T, ctx_len, out_dev,
+                  st);
+    enqueue_compact(c, kv, layer_begin, layer_end, ctx_len, out_dev, st);
     HIP_TRY(hipGetLastError());
     if (out_host) {
         HIP_TRY(hipMemcpyAsync(out_host, out_dev, sizeof(cats_accept_result), hipMemcpyDeviceToHost, st));
@@ -375,6 +410,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_amax = take(Tm * 4);
     const size_t o_sb = take(Tm * ARGMAX_SLICES * 4), o_s2 = take(Tm * ARGMAX_SLICES * 4);
     const size_t o_si = take(Tm * ARGMAX_SLICES * 4), o_arr = take(Tm * 4);   // zero from the memset below
+    const size_t o_tl = take(Tm * 4), o_te = take(Tm * 4), o_ts = take(Tm * ARGMAX_SLICES * 3 * 4);
+    const size_t o_tp = take(Tm * 4), o_tt = take(Tm * 4), o_tg = take(Tm);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->flat), off);
     if (e != hipSuccess) {
         delete c;
@@ -410,6 +447,12 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->am_second = reinterpret_cast<float*>(b + o_s2);
     c->am_idx = reinterpret_cast<int*>(b + o_si);
     c->am_arrivals = reinterpret_cast<int*>(b + o_arr);
+    c->typ_lse = reinterpret_cast<float*>(b + o_tl);
+    c->typ_entropy = reinterpret_cast<float*>(b + o_te);
+    c->typ_slice = reinterpret_cast<float*>(b + o_ts);
+    c->typ_prob = reinterpret_cast<float*>(b + o_tp);
+    c->typ_thr = reinterpret_cast<float*>(b + o_tt);
+    c->typ_edge = reinterpret_cast<uint8_t*>(b + o_tg);
     *out = c;
     return CATS_OK;
 }
@@ -590,9 +633,48 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     if (hidden_out)
         HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
     int32_t* amax = argmax_out ? argmax_out : ctx->amax;
-    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
+    const bool typical = ctx->accept_mode == 1;
+    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st, typical);
     HIP_TRY(hipGetLastError());
-    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
+    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st,
+                                  typical);
+}
+
+int cats_set_acceptance(cats_ctx* ctx, int32_t mode, float epsilon, float delta, float temperature) {
+    if (!ctx || (mode != 0 && mode != 1)) return CATS_EINVAL;
+    if (mode == 1 && !(epsilon >= 0.f && delta >= 0.f && temperature > 0.f)) return CATS_EINVAL;
+    ctx->accept_mode = mode;
+    if (mode == 1) {
+        ctx->typ_epsilon = epsilon;
+        ctx->typ_delta = delta;
+        ctx->typ_inv_temp = 1.f / temperature;
+    }
+    return CATS_OK;
+}
+
+int cats_typical_stats(cats_ctx* ctx, float* lse_out, float* entropy_out, float* prob_out, float* threshold_out,
+                       void* stream) {
+    if (!ctx) return CATS_EINVAL;
+    if (ctx->T < 1) return CATS_ESTATE;
+    hipStream_t st = as_stream(stream);
+    const size_t bytes = sizeof(float) * ctx->T;
+    const float* src[4] = {ctx->typ_lse, ctx->typ_entropy, ctx->typ_prob, ctx->typ_thr};
+    float* dst[4] = {lse_out, entropy_out, prob_out, threshold_out};
+    for (int i = 0; i < 4; ++i)
+        if (dst[i]) HIP_TRY(hipMemcpyAsync(dst[i], src[i], bytes, hipMemcpyDeviceToDevice, st));
+    return CATS_OK;
+}
+
+int cats_compact_along(cats_ctx* ctx, const cats_accept_result* result_dev, const cats_kv_layer* kv,
+                       int32_t layer_begin, int32_t layer_end, int32_t ctx_len, void* stream) {
+    const int rc = check_ctx_len(ctx, ctx_len);
+    if (rc != CATS_OK) return rc;
+    if (!result_dev || layer_begin < 0 || layer_end < layer_begin || layer_end > ctx->d.n_layers)
+        return CATS_EINVAL;
+    if (layer_end > layer_begin && !kv_ok(kv, layer_begin, layer_end)) return CATS_EINVAL;
+    enqueue_compact(ctx, kv, layer_begin, layer_end, ctx_len, result_dev, as_stream(stream));
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
 }
 
 int cats_verify_nodes(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
@@ -795,9 +877,11 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
     if (hidden_out)
         HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
     int32_t* amax = argmax_out ? argmax_out : ctx->amax;
-    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st);
+    const bool typical = ctx->accept_mode == 1;
+    enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st, typical);
     HIP_TRY(hipGetLastError());
-    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st);
+    return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st,
+                                  typical);
 }
 
 const char* cats_gemm_kernel_name(void) { return "cats_gemm_skinny_bf16"; }

@@ -208,6 +208,12 @@ struct ArgmaxArgs {
     float* slice_second;
     int* slice_idx;
     int* arrivals;
+    // optional (typical acceptance): log-sum-exp and entropy of softmax(logits * inv_temp) per
+    // node, from per-slice (max, sum of exponentials, exponential-weighted sum) triples
+    float inv_temp;
+    float* lse;             // [T] or null
+    float* entropy;         // [T]
+    float* slice_stat;      // [T][ARGMAX_SLICES][3]
 };
 constexpr int ARGMAX_SLICES = 16;
 void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
@@ -240,8 +246,24 @@ void launch_tree_upload(const TreeUploadArgs& a, int n, int32_t* token, int32_t*
                         int32_t* depth, hipStream_t st);
 
 void launch_accept(const int32_t* token, const int32_t* parent, const int32_t* depth,
-                   const int32_t* amax, int T, int ctx_len, cats_accept_result* out,
-                   hipStream_t st);
+                   const int32_t* amax, const uint8_t* edge_ok, int T, int ctx_len,
+                   cats_accept_result* out, hipStream_t st);
+
+struct TypicalArgs {
+    const int32_t* token;
+    const int32_t* parent;
+    const float* part;      // LM-head partial tiles [pieces][T][ld]
+    GemmPlan plan;
+    NormScale ns;
+    int T, ld;
+    const float* lse;       // [T] log-sum-exp of logits / temperature
+    const float* entropy;   // [T] entropy of softmax(logits / temperature)
+    float inv_temp, epsilon, delta;
+    uint8_t* edge_ok;       // [T]
+    float* prob;            // [T] probability of the node's token under its parent
+    float* thr;             // [T] threshold at its parent
+};
+void launch_typical_edges(const TypicalArgs& a, hipStream_t st);
 
 struct CompactArgs {
     bf16_t* k[CATS_MAX_LAYERS];

@@ -195,10 +195,14 @@ __device__ __forceinline__ void top2_merge(float& b, int& bi, float& s2, float o
 __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
     __shared__ float s_best[AM_THREADS / 64], s_second[AM_THREADS / 64];
     __shared__ int s_idx[AM_THREADS / 64];
+    __shared__ float s_stat[AM_THREADS / 64][3];
     const int t = blockIdx.x, slice = blockIdx.y, tid = threadIdx.x;
     float best = -INFINITY, second = -INFINITY;
     int bidx = 0x7fffffff;
     const float rs = row_scale(a.ns, t);
+    // running (max, sum exp, sum exp * z) of z = logit * inv_temp for the log-sum-exp and the entropy
+    const bool stats = a.lse != nullptr;
+    float zm = -INFINITY, zs = 0.f, zw = 0.f;
     auto take = [&](float val, int v) {   // indices ascend within a thread: strict > keeps the lowest
         if (val > best) {
             second = best;
@@ -207,6 +211,26 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
         } else if (val > second) {
             second = val;
         }
+        if (stats) {
+            const float z = val * a.inv_temp;
+            if (z > zm) {
+                const float c = __expf(zm - z);   // 0 on the first element (zm = -inf)
+                zs = zs * c + 1.f;
+                zw = zw * c + z;
+                zm = z;
+            } else {
+                const float e = __expf(z - zm);
+                zs += e;
+                zw += e * z;
+            }
+        }
+    };
+    auto stat_merge = [](float& m, float& s1, float& w, float om, float os, float ow) {
+        const float mn = fmaxf(m, om);
+        const float ca = m == mn ? 1.f : __expf(m - mn), cb = om == mn ? 1.f : __expf(om - mn);
+        s1 = s1 * ca + os * cb;
+        w = w * ca + ow * cb;
+        m = mn;
     };
     if (a.ld % 4 == 0) {
         const int groups = (a.V + 3) / 4;
@@ -244,15 +268,22 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
         const float ob = __shfl_xor(best, o), os = __shfl_xor(second, o);
         const int oi = __shfl_xor(bidx, o);
         top2_merge(best, bidx, second, ob, oi, os);
+        if (stats) stat_merge(zm, zs, zw, __shfl_xor(zm, o), __shfl_xor(zs, o), __shfl_xor(zw, o));
     }
     if ((tid & 63) == 0) {
         s_best[tid >> 6] = best;
         s_second[tid >> 6] = second;
         s_idx[tid >> 6] = bidx;
+        s_stat[tid >> 6][0] = zm;
+        s_stat[tid >> 6][1] = zs;
+        s_stat[tid >> 6][2] = zw;
     }
     __syncthreads();
     if (tid != 0) return;
-    for (int w = 1; w < AM_THREADS / 64; ++w) top2_merge(best, bidx, second, s_best[w], s_idx[w], s_second[w]);
+    for (int w = 1; w < AM_THREADS / 64; ++w) {
+        top2_merge(best, bidx, second, s_best[w], s_idx[w], s_second[w]);
+        if (stats) stat_merge(zm, zs, zw, s_stat[w][0], s_stat[w][1], s_stat[w][2]);
+    }
     // publish this slice; the last arriver of the node merges.  The slice results move with
     // device-coherent (relaxed, device-scope) atomic stores and loads, which bypass the
     // per-XCD caches; waiting for the stores' acknowledgement before the arrival count is
@@ -263,6 +294,12 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
     __hip_atomic_store(pb + slice, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(ps + slice, second, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(pi + slice, bidx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    float* pst = a.slice_stat + (static_cast<size_t>(t) * AM_SLICES + slice) * 3;
+    if (stats) {
+        __hip_atomic_store(pst, zm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pst + 1, zs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pst + 2, zw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     const int arrived = __hip_atomic_fetch_add(a.arrivals + t, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("" ::: "memory");
@@ -276,6 +313,19 @@ __global__ __launch_bounds__(AM_THREADS) void cats_argmax(ArgmaxArgs a) {
                    __hip_atomic_load(ps + sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     a.amax[t] = bidx;
     if (a.margin) a.margin[t] = best - second;
+    if (stats) {
+        const float* ps0 = a.slice_stat + static_cast<size_t>(t) * AM_SLICES * 3;
+        zm = -INFINITY;
+        zs = 0.f;
+        zw = 0.f;
+        for (int sl = 0; sl < AM_SLICES; ++sl)
+            stat_merge(zm, zs, zw, __hip_atomic_load(ps0 + 3 * sl, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                       __hip_atomic_load(ps0 + 3 * sl + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                       __hip_atomic_load(ps0 + 3 * sl + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        const float lse = zm + logf(zs);
+        a.lse[t] = lse;
+        a.entropy[t] = lse - zw / zs;   // H = -sum p log p = lse - sum p z
+    }
     __hip_atomic_store(a.arrivals + t, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
