@@ -18,13 +18,13 @@ struct cats_ctx {
     u32x4* anc;  // [max_tree] ancestor-or-self masks of the uploaded tree
     int32_t h_parent[CATS_MAX_TREE], h_depth[CATS_MAX_TREE];
     int T;  // 0 = no tree set
-    int n0 = 0;  // first node of the range being forwarded (0 except inside cats_verify_nodes)
+    // the call being enqueued (set by every entry point before its helpers run): the row
+    // kernels and GEMMs work on `rows` rows, which are nodes n0 .. n0 + rows - 1 of the tree
+    int n0 = 0;
+    int rows = 0;
     // acceptance criterion of cats_verify_tree[_streamed]: 0 greedy, 1 typical
     int accept_mode = 0;
     float typ_epsilon = 0.09f, typ_delta = 0.3f, typ_inv_temp = 1.f;
-    float *typ_lse = nullptr, *typ_entropy = nullptr, *typ_slice = nullptr, *typ_prob = nullptr, *typ_thr = nullptr;
-    uint8_t* typ_edge = nullptr;
-    int rows = 0;  // rows the row kernels and GEMMs of the call being enqueued work on (set by every entry point)
     // scratch
     float* x;        // [max_tree][H] residual stream
     // activations that feed a GEMM or the attention products: high and low bf16 parts
@@ -42,6 +42,10 @@ struct cats_ctx {
     int32_t* amax;   // [max_tree]
     float *am_best, *am_second;   // [max_tree][ARGMAX_SLICES] slice results of the argmax
     int *am_idx, *am_arrivals;    // [max_tree][ARGMAX_SLICES] indices, [max_tree] arrival counters (zero between launches)
+    // typical acceptance: per node log-sum-exp, entropy, per-slice triples behind them; per node
+    // probability of its token at its parent, the threshold there, and the decision
+    float *typ_lse = nullptr, *typ_entropy = nullptr, *typ_slice = nullptr, *typ_prob = nullptr, *typ_thr = nullptr;
+    uint8_t* typ_edge = nullptr;
     char* flat;      // the single allocation behind all of the above
     // offload regime: copy stream and the events that order it against the compute stream
     hipStream_t copy_stream;
