@@ -241,7 +241,7 @@ int cats_build_tree(int32_t root_token, const int32_t *main_tokens, int32_t gamm
  * Logits must be finite.  Enqueues on `stream` and returns; nothing is allocated.
  * CATS_EINVAL: NULL required pointer, misaligned pointer, n_pos < 1, vocab not a positive
  * multiple of 4, top_k outside [1, min(CATS_LOSS_MAX_K, vocab)]; CATS_ECAPACITY: vocab above
- * CATS_LOSS_MAX_VOCAB (the target row is kept in one workgroup's LDS). */
+ * CATS_LOSS_MAX_VOCAB (a whole row is held in one workgroup's registers). */
 #define CATS_LOSS_MAX_K 64
 #define CATS_LOSS_MAX_VOCAB 36864
 int cats_reduced_kl_loss(const float *target_logits, const float *draft_logits, const uint8_t *mask,

@@ -7,14 +7,15 @@
 // loss_t = -sum_{v in T_K} p~_v log q_v with log q_v = z_v - logsumexp(z).  The loss is the mean
 // of loss_t over the unmasked positions; d loss / d z_v = (q_v - p~_v) / |M|.
 //
-// One workgroup of 1024 threads per position; both logit rows are read from HBM exactly once:
-// the target row goes to LDS (the selection looks at it again), the draft row stays in
-// registers (vocab / 1024 values per thread), so the gradient row is written without a second
-// read.  Selection without sorting the row: the K-th largest of the
-// maxima of 256 thread groups is a lower bound L of the K-th largest value (K groups have a
+// One workgroup of 512 threads per position, two workgroups per compute unit; each logit row is
+// read from HBM exactly once and only one row is held (in registers, vocab / 512 values per
+// thread) at a time: first the draft row (log-sum-exp, then the dense part q / |M| of the
+// gradient row goes out), then the target row (selection, loss, and the K entries of the
+// gradient that also carry -p~ / |M|).  Selection without sorting the row: the K-th largest of
+// the maxima of 128 thread groups is a lower bound L of the K-th largest value (K groups have a
 // value at or above it); the few elements >= L are gathered in LDS and ranked exactly (value
 // descending, index ascending).  Rows with very many values >= L (e.g. all equal) take a slow
-// exact path that ranks against the whole row.  Every sum has a fixed order: results
+// exact path that ranks against the whole row in memory.  Every sum has a fixed order: results
 // do not change from run to run.  The two per-element exponentials (log-sum-exp, q in the
 // gradient) use the hardware exp2 (relative error about |x| * 1e-7 for an argument x <= 0);
 // the K selected terms use the accurate expf.
@@ -24,7 +25,7 @@
 
 namespace {
 
-constexpr int LOSS_NT = 1024;    // threads per workgroup
+constexpr int LOSS_NT = 512;     // threads per workgroup
 constexpr int LOSS_CAP = 1024;   // candidates ranked on the fast path
 constexpr int LOSS_WAVES = LOSS_NT / 64;
 constexpr int LOSS_GROUPS = LOSS_NT / 4;   // thread groups whose maxima bound the selection
@@ -47,16 +48,17 @@ __device__ __forceinline__ bool before(float b, int ib, float a, int ia) {
     return b > a || (b == a && ib < ia);
 }
 
-// LOSS_MAXI: 16-byte pieces per thread and row the registers are laid out for (>= vocab / 4096).
+// LOSS_MAXI: 16-byte pieces per thread the registers are laid out for (>= vocab / 2048); piece j
+// of a thread is 16-byte piece tid + j * 512 of the row.  (The second launch bound is waves per
+// SIMD: four, so that two workgroups share a compute unit and one's arithmetic hides behind the
+// other's memory traffic.)
 template <int LOSS_MAXI>
-__global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a) {
-    extern __shared__ __align__(16) float s_row[];   // the target row, V floats
+__global__ __launch_bounds__(LOSS_NT, 4) void cats_reduced_kl_positions(LossArgs a) {
     __shared__ __align__(16) float s_gmax[LOSS_GROUPS];
     __shared__ float s_cval[LOSS_CAP];
     __shared__ int s_cidx[LOSS_CAP];
     __shared__ float s_sval[CATS_LOSS_MAX_K];
     __shared__ int s_sidx[CATS_LOSS_MAX_K];
-    __shared__ float s_pt[CATS_LOSS_MAX_K];
     __shared__ float s_m[LOSS_WAVES], s_s[LOSS_WAVES], s_L;
     __shared__ int s_cnt[LOSS_WAVES], s_ncand;
 
@@ -72,54 +74,30 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
                 reinterpret_cast<f32x4*>(a.grad + row)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         return;
     }
-
-    // ---- both rows into registers: piece j of this thread is 16-byte piece tid + j * 1024
-    const f32x4* tg = reinterpret_cast<const f32x4*>(a.target + row);
-    const f32x4* dr = reinterpret_cast<const f32x4*>(a.draft + row);
     // (uniform row base + 32-bit byte offset: one address register per load)
-    const char* tg_bytes = reinterpret_cast<const char*>(tg);
-    const char* dr_bytes = reinterpret_cast<const char*>(dr);
-    f32x4 av[LOSS_MAXI], zv[LOSS_MAXI];
+    const char* tg_bytes = reinterpret_cast<const char*>(a.target + row);
+    const char* dr_bytes = reinterpret_cast<const char*>(a.draft + row);
+    f32x4 rv[LOSS_MAXI];   // the row in hand: first the draft row, then the target row
+
+    // ================= draft row: log-sum-exp, dense part of the gradient =================
 #pragma unroll
     for (int j = 0; j < LOSS_MAXI; ++j) {
         const unsigned off = 16u * static_cast<unsigned>(min(tid + j * LOSS_NT, V4 - 1));
-        av[j] = *reinterpret_cast<const f32x4*>(tg_bytes + off);
-    }
-#pragma unroll
-    for (int j = 0; j < LOSS_MAXI; ++j) {
-        const unsigned off = 16u * static_cast<unsigned>(min(tid + j * LOSS_NT, V4 - 1));
-        zv[j] = *reinterpret_cast<const f32x4*>(dr_bytes + off);
-    }
-    float a_max = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < LOSS_MAXI; ++j) {
-        const int i = tid + j * LOSS_NT;
-        if (i < V4) {
-            reinterpret_cast<f32x4*>(s_row)[i] = av[j];
-            a_max = fmaxf(fmaxf(fmaxf(a_max, av[j][0]), fmaxf(av[j][1], av[j][2])), av[j][3]);
-        }
+        rv[j] = *reinterpret_cast<const f32x4*>(dr_bytes + off);
     }
     int n_unmasked = 0;
-    if (a.mask)
+    if (a.mask && a.grad)
         for (int i = tid; i < a.P; i += LOSS_NT) n_unmasked += a.mask[i] != 0;
-
-    // ---- own maxima; log-sum-exp of the draft row (thread, wave, workgroup: fixed order)
     float m = -INFINITY;
 #pragma unroll
     for (int j = 0; j < LOSS_MAXI; ++j) {
-        if (tid + j * LOSS_NT < V4) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) m = fmaxf(m, zv[j][e]);
-        }
+        if (tid + j * LOSS_NT < V4) m = fmaxf(fmaxf(fmaxf(m, rv[j][0]), fmaxf(rv[j][1], rv[j][2])), rv[j][3]);
     }
-    float gmax = fmaxf(a_max, __shfl_xor(a_max, 1));
-    gmax = fmaxf(gmax, __shfl_xor(gmax, 2));
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         m = fmaxf(m, __shfl_xor(m, off));
         n_unmasked += __shfl_xor(n_unmasked, off);
     }
-    if ((tid & 3) == 0) s_gmax[tid >> 2] = gmax;
     if (lane == 0) {
         s_m[wave] = m;
         s_cnt[wave] = n_unmasked;
@@ -127,31 +105,68 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
     if (tid == 0) s_ncand = 0;
     __syncthreads();
     float z_max = s_m[0];
-    {
-        int n = s_cnt[0];
-        for (int w = 1; w < LOSS_WAVES; ++w) {
-            z_max = fmaxf(z_max, s_m[w]);
-            n += s_cnt[w];
-        }
-        n_unmasked = a.mask ? n : a.P;
+    n_unmasked = s_cnt[0];
+    for (int w = 1; w < LOSS_WAVES; ++w) {
+        z_max = fmaxf(z_max, s_m[w]);
+        n_unmasked += s_cnt[w];
     }
+    if (!a.mask) n_unmasked = a.P;
     float s = 0.f;
 #pragma unroll
     for (int j = 0; j < LOSS_MAXI; ++j) {
         if (tid + j * LOSS_NT < V4) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) s += __expf(zv[j][e] - z_max);
+            for (int e = 0; e < 4; ++e) s += __expf(rv[j][e] - z_max);
         }
     }
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) s += __shfl_xor(s, off);
     if (lane == 0) s_s[wave] = s;
+    __syncthreads();
+    float lse;
+    {
+        float S = 0.f;
+        for (int w = 0; w < LOSS_WAVES; ++w) S += s_s[w];
+        lse = z_max + logf(S);
+    }
+    const float inv_n = 1.f / static_cast<float>(n_unmasked);
+    if (a.grad) {   // q / |M| everywhere; the K selected entries get their -p~ / |M| at the end
+        char* gr_bytes = reinterpret_cast<char*>(a.grad + row);
+#pragma unroll
+        for (int j = 0; j < LOSS_MAXI; ++j) {
+            const int i = tid + j * LOSS_NT;
+            if (i < V4) {
+                f32x4 g;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) g[e] = __expf(rv[j][e] - lse) * inv_n;
+                *reinterpret_cast<f32x4*>(gr_bytes + 16u * static_cast<unsigned>(i)) = g;
+            }
+        }
+    }
+
+    // ================= target row: selection, loss =================
+#pragma unroll
+    for (int j = 0; j < LOSS_MAXI; ++j) {
+        const unsigned off = 16u * static_cast<unsigned>(min(tid + j * LOSS_NT, V4 - 1));
+        rv[j] = *reinterpret_cast<const f32x4*>(tg_bytes + off);
+    }
+    float a_max = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < LOSS_MAXI; ++j) {
+        if (tid + j * LOSS_NT < V4)
+            a_max = fmaxf(fmaxf(fmaxf(a_max, rv[j][0]), fmaxf(rv[j][1], rv[j][2])), rv[j][3]);
+    }
+    float gmax = fmaxf(a_max, __shfl_xor(a_max, 1));
+    gmax = fmaxf(gmax, __shfl_xor(gmax, 2));
+    if ((tid & 3) == 0) s_gmax[tid >> 2] = gmax;
+    __syncthreads();
 
     // ---- lower bound L of the K-th largest value: the K-th largest group maximum.  The four
     //      threads of a group each compare against a quarter of the groups.
     {
         const int g = tid >> 2, q = tid & 3;
         int rank = 0;
+#pragma unroll 2
         for (int j = q * (LOSS_GROUPS / 4); j < (q + 1) * (LOSS_GROUPS / 4); j += 4) {
             const f32x4 o = *reinterpret_cast<const f32x4*>(s_gmax + j);
 #pragma unroll
@@ -163,27 +178,18 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
     }
     __syncthreads();
     const float L = s_L;
-    float lse;
-    {
-        float S = 0.f;
-        for (int w = 0; w < LOSS_WAVES; ++w) S += s_s[w];
-        lse = z_max + logf(S);
-    }
 
-    // ---- gather the elements >= L; from here on one bit per own element stands for the target row
-    uint64_t cand_bits = 0;
+    // ---- gather the elements >= L
 #pragma unroll
     for (int j = 0; j < LOSS_MAXI; ++j) {
         const int i = tid + j * LOSS_NT;
         if (i < V4) {
-            const f32x4 mine = reinterpret_cast<const f32x4*>(s_row)[i];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (mine[e] >= L) {
-                    cand_bits |= 1ull << (4 * j + e);
+                if (rv[j][e] >= L) {
                     const int slot = atomicAdd(&s_ncand, 1);
                     if (slot < LOSS_CAP) {
-                        s_cval[slot] = mine[e];
+                        s_cval[slot] = rv[j][e];
                         s_cidx[slot] = 4 * i + e;
                     }
                 }
@@ -205,16 +211,17 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
                 s_sidx[rank] = idx;
             }
         }
-    } else {   // slow exact path: rank every element >= L against the whole row
+    } else {   // slow exact path: rank every element >= L against the whole row in memory
+        const f32x4* tg = reinterpret_cast<const f32x4*>(tg_bytes);
         for (int i = tid; i < V4; i += LOSS_NT) {
-            const f32x4 mine = reinterpret_cast<const f32x4*>(s_row)[i];
+            const f32x4 mine = tg[i];
             for (int e = 0; e < 4; ++e) {
                 const float val = e == 0 ? mine[0] : (e == 1 ? mine[1] : (e == 2 ? mine[2] : mine[3]));
                 if (val >= L) {
                     const int idx = 4 * i + e;
                     int rank = 0;
                     for (int u = 0; u < V4 && rank < K; ++u) {
-                        const f32x4 o = reinterpret_cast<const f32x4*>(s_row)[u];
+                        const f32x4 o = tg[u];
 #pragma unroll
                         for (int f = 0; f < 4; ++f) rank += before(o[f], 4 * u + f, val, idx);
                     }
@@ -228,13 +235,16 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
     }
     __syncthreads();
 
-    // ---- the K terms of the loss (one wave; lane = rank)
+    // ---- the K terms of the loss and of the gradient (one wave; lane = rank).  The dense
+    //      gradient stores of every wave were complete before the barriers above.
     if (wave == 0) {
         float w = 0.f, num = 0.f;
+        int idx = 0;
         if (lane < K) {
+            idx = s_sidx[lane];
             w = expf(s_sval[lane] - s_sval[0]);
-            num = w * a.draft[row + s_sidx[lane]];
-            if (a.topk) a.topk[static_cast<size_t>(t) * K + lane] = s_sidx[lane];
+            num = w * a.draft[row + idx];
+            if (a.topk) a.topk[static_cast<size_t>(t) * K + lane] = idx;
         }
         float den = w;
 #pragma unroll
@@ -243,32 +253,7 @@ __global__ __launch_bounds__(LOSS_NT) void cats_reduced_kl_positions(LossArgs a)
             den += __shfl_xor(den, off);
         }
         if (lane == 0) a.per_pos[t] = lse - num / den;
-        if (lane < K) s_pt[lane] = w / den;   // p~ of the selected tokens
-    }
-    if (!a.grad) return;
-    __syncthreads();
-
-    // ---- gradient row: (q - p~) / |M|.  q for every element first; the few elements flagged as
-    //      candidates then look themselves up among the K selected tokens (same thread, same
-    //      address: program order holds).
-    const float inv_n = 1.f / static_cast<float>(n_unmasked);
-    char* gr_bytes = reinterpret_cast<char*>(a.grad + row);
-#pragma unroll
-    for (int j = 0; j < LOSS_MAXI; ++j) {
-        const int i = tid + j * LOSS_NT;
-        if (i < V4) {
-            f32x4 g;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) g[e] = __expf(zv[j][e] - lse) * inv_n;
-            *reinterpret_cast<f32x4*>(gr_bytes + 16u * static_cast<unsigned>(i)) = g;
-        }
-    }
-    while (cand_bits) {
-        const int b = __builtin_ctzll(cand_bits);
-        cand_bits &= cand_bits - 1;
-        const int idx = 4 * (tid + (b >> 2) * LOSS_NT) + (b & 3);
-        for (int r = 0; r < K; ++r)
-            if (s_sidx[r] == idx) a.grad[row + idx] -= s_pt[r] * inv_n;
+        if (a.grad && lane < K) a.grad[row + idx] -= (w / den) * inv_n;
     }
 }
 
@@ -307,23 +292,6 @@ __global__ __launch_bounds__(1024) void cats_reduced_kl_mean(const float* per_po
     }
 }
 
-// The target row needs more dynamic LDS than the default limit: raised once per kernel variant.
-template <int MAXI>
-int launch_positions(const LossArgs& a, size_t lds, hipStream_t st) {
-    static bool limit_raised = false;
-    if (!limit_raised) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(cats_reduced_kl_positions<MAXI>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(sizeof(float) * CATS_LOSS_MAX_VOCAB)) != hipSuccess) {
-            (void)hipGetLastError();
-            return CATS_EHIP;
-        }
-        limit_raised = true;
-    }
-    hipLaunchKernelGGL(cats_reduced_kl_positions<MAXI>, dim3(a.P), dim3(LOSS_NT), lds, st, a);
-    return CATS_OK;
-}
-
 }  // namespace
 
 extern "C" int cats_reduced_kl_loss(const float* target_logits, const float* draft_logits, const uint8_t* mask,
@@ -339,15 +307,12 @@ extern "C" int cats_reduced_kl_loss(const float* target_logits, const float* dra
     hipStream_t st = static_cast<hipStream_t>(stream);
     LossArgs a{target_logits, draft_logits, mask, n_pos, vocab, top_k, per_pos_out, topk_idx_out, grad_out};
     const int pieces = (vocab / 4 + LOSS_NT - 1) / LOSS_NT;
-    const size_t lds = sizeof(float) * static_cast<size_t>(vocab);
-    int rc;
-    if (pieces <= 2)
-        rc = launch_positions<2>(a, lds, st);
-    else if (pieces <= 8)
-        rc = launch_positions<8>(a, lds, st);
+    if (pieces <= 4)
+        hipLaunchKernelGGL(cats_reduced_kl_positions<4>, dim3(n_pos), dim3(LOSS_NT), 0, st, a);
+    else if (pieces <= 16)
+        hipLaunchKernelGGL(cats_reduced_kl_positions<16>, dim3(n_pos), dim3(LOSS_NT), 0, st, a);
     else
-        rc = launch_positions<LOSS_MAXI_TOP>(a, lds, st);
-    if (rc != CATS_OK) return rc;
+        hipLaunchKernelGGL(cats_reduced_kl_positions<LOSS_MAXI_TOP>, dim3(n_pos), dim3(LOSS_NT), 0, st, a);
     hipLaunchKernelGGL(cats_reduced_kl_mean, dim3(1), dim3(1024), 0, st, per_pos_out, mask, n_pos, loss_out);
     return hipGetLastError() == hipSuccess ? CATS_OK : CATS_EHIP;
 }
