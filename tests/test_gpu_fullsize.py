@@ -148,3 +148,28 @@ def test_7b_layer_shape_cascaded_cycle():
         check_cycle(pair, kc, vc, S, 4242, drafts, corrections, 1)
     finally:
         pair.close()
+
+
+def test_largest_supported_layer_shape_and_deepest_tree():
+    """The limits of the library in one case: hidden 8192 (the widest the norm scratch allows), 64
+    heads of 128, a 128-node tree (CATS_MAX_TREE) that reaches depth 16 (CATS_MAX_DEPTH), one
+    layer, a ragged context length."""
+    dims = synth.ModelDims(1, 8192, 64, 128, 28672, 32000)
+    T, S = 128, 1003
+    # a chain down to the depth limit, the other nodes hung on random earlier nodes above it
+    rng = np.random.default_rng(21)
+    parent = np.full(T, -1, dtype=np.int32)
+    depth = np.zeros(T, dtype=np.int32)
+    for i in range(1, T):
+        if i <= 16:
+            parent[i] = i - 1
+        else:
+            parent[i] = int(rng.choice([j for j in range(i) if depth[j] < 16]))
+        depth[i] = depth[parent[i]] + 1
+    assert synth.is_valid_tree(parent, depth) and depth.max() == 16
+    pair = Pair(dims, 5, max_ctx=1152, max_tree=128, precision="f32", n_layers=1, packed=True)
+    try:
+        tok = synth.distinct_sibling_tokens(parent, dims.vocab, 3)
+        compare_with_oracle(pair, S, tok, parent, depth, 9)
+    finally:
+        pair.close()
