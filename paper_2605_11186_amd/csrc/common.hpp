@@ -84,13 +84,9 @@ size_t packed_matrix_elems(int rows, int cols);
 #ifndef CATS_GEMM_ST
 #define CATS_GEMM_ST 2
 #endif
-#ifndef CATS_GEMM_ST4
-#define CATS_GEMM_ST4 2
-#endif
 constexpr int GEMM_BN = CATS_GEMM_BN;    // weight rows per workgroup (32 per wave)
 constexpr int GEMM_KC = 128;             // k elements per pipeline stage
 constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
-constexpr int GEMM_ST4 = CATS_GEMM_ST4;  // ... for T > 64 (larger accumulators)
 GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn);   // bn: 256 or 128 weight rows per tile
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
