@@ -132,7 +132,7 @@ int cats_set_tree(cats_ctx *ctx, const cats_tree *tree, void *stream);
 int cats_verify_layer(cats_ctx *ctx, const cats_layer_weights *w, float *hidden,
                       const cats_kv_layer *kv, int32_t ctx_len, void *stream);
 
-/* Tree-masked attention alone (Fig. 4 right-lower; "tree attention mask" of the
+/* Tree-masked attention alone (Fig. 4 right-lower; the tree attention mask of the
  * target verification pass).  q: bf16 [T][hidden], already rotated; kv rows
  * ctx_len .. ctx_len+T-1 must already hold the tree nodes' keys/values.
  * out: bf16 [T][hidden].  Node i sees rows [0, ctx_len) and rows ctx_len + a
@@ -140,9 +140,8 @@ int cats_verify_layer(cats_ctx *ctx, const cats_layer_weights *w, float *hidden,
 int cats_tree_attention(cats_ctx *ctx, const void *q, const cats_kv_layer *kv, int32_t ctx_len,
                         void *out, void *stream);
 
-/* Greedy acceptance and KV roll-back (Algorithm 1: "Walk the tree to find the
- * longest accepted prefix", bonus token, "Roll back KV ... along the accepted
- * path").  node_argmax: int32 [T], the target's greedy token at every node.
+/* Greedy acceptance and KV roll-back (Algorithm 1: the walk over the tree for the longest
+ * accepted prefix, the bonus token, and the roll-back of the KV cache along the accepted path).  node_argmax: int32 [T], the target's greedy token at every node.
  * kv: HOST array indexed by layer; layers [layer_begin, layer_end) are
  * compacted: row ctx_len + path[k] moves to row ctx_len + k.  Rows from
  * new_ctx_len on are left undefined.  out_dev: device result (required);
@@ -154,7 +153,7 @@ int cats_accept_and_compact(cats_ctx *ctx, const int32_t *node_argmax, const cat
 
 /* A whole verify step: input rows (embedding lookup of the tree tokens when
  * `embed` [vocab][hidden] bf16 is given, else `hidden_in` float32 [T][hidden],
- * the stage-3 "T.hidden_states"), layers [layer_begin, layer_end) of `layers`
+ * the hidden states of the tree that Alg. 1 hands to stage 3), layers [layer_begin, layer_end) of `layers`
  * (HOST array indexed by layer), final RMSNorm (g_final) + LM head (w_lm
  * [vocab][hidden]) + per-node argmax, then acceptance and compaction as above.
  * Optional device outputs: hidden_out float32 [T][hidden] (residual stream after
@@ -168,7 +167,7 @@ int cats_verify_tree(cats_ctx *ctx, const cats_layer_weights *layers, int32_t la
                      void *stream);
 
 /* Acceptance criterion Acc of the walk in cats_verify_tree / cats_verify_tree_streamed (Alg. 1:
- * "greedy or typical"; Sec. 3.2 names typical acceptance by citation only, so the inequality is
+ * Acc may be greedy or typical; Sec. 3.2 names typical acceptance by citation only, so the inequality is
  * the cited work's: a candidate token x judged at its parent's distribution
  * p = softmax(logits / temperature) passes when p(x) > min(epsilon, delta * exp(-H(p))), H the
  * entropy of p).  mode 0 = greedy (the default: the token must equal the parent's argmax), mode
@@ -186,15 +185,15 @@ int cats_set_acceptance(cats_ctx *ctx, int32_t mode, float epsilon, float delta,
 int cats_typical_stats(cats_ctx *ctx, float *lse_out, float *entropy_out, float *prob_out,
                        float *threshold_out, void *stream);
 
-/* KV roll-back alone along an accept result that already exists on the device (Alg. 1: "Roll
- * back KV ... along the accepted path"): rows ctx_len + path[k] -> ctx_len + k, k = 0..n_accepted,
+/* KV roll-back alone along an accept result that already exists on the device (Alg. 1, the
+ * roll-back line at the end of a cycle): rows ctx_len + path[k] -> ctx_len + k, k = 0..n_accepted,
  * in layers [layer_begin, layer_end) of kv (HOST array indexed by layer).  For caches that the
  * call which produced result_dev did not cover: the shallow layers of a staged cycle, adapter
  * caches. */
 int cats_compact_along(cats_ctx *ctx, const cats_accept_result *result_dev, const cats_kv_layer *kv,
                        int32_t layer_begin, int32_t layer_end, int32_t ctx_len, void *stream);
 
-/* Shallow-verification stage, correction re-forward (Sec. 3.2 "shallow verification"; Alg. 1,
+/* Shallow-verification stage, correction re-forward (Sec. 3.2, shallow verification stage; Alg. 1,
  * stage 2: the correction tokens are forwarded again through the resident layers under the tree
  * mask while the main draft chain is not).  Forwards only nodes [node_begin, T) of the tree set
  * by cats_set_tree through layers [layer_begin, layer_end): their queries see the KV context and
@@ -248,8 +247,8 @@ int cats_reduced_kl_loss(const float *target_logits, const float *draft_logits, 
                          int32_t n_pos, int32_t vocab, int32_t top_k, float *loss_out,
                          float *per_pos_out, int32_t *topk_idx_out, float *grad_out, void *stream);
 
-/* Offload regime (Sec. 3.2: the target layers are "streamed ... chunk by chunk" while the
- * previous chunk computes; Fig. 4 left): the same verify step with the layer weights held
+/* Offload regime (Sec. 3.2: the target layers arrive from slower memory one chunk after the
+ * other while the previous chunk computes; Fig. 4 left): the same verify step with the layer weights held
  * in pinned HOST memory.  host_layers: HOST array indexed by layer whose nine pointers are
  * pinned HOST addresses (packed matrices if the context was created with packed_weights).
  * staging[0..1]: two DEVICE buffers of cats_layer_weight_bytes() each; layer l is copied into staging[l & 1] on the context's own copy stream while layer

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY: imported by the tests.  The GPU library never imports or calls this.
 
-The paper names the criterion only by citation (Sec. 3.2 and Alg. 1: "greedy or typical", citing
+The paper names the criterion only by citation (Sec. 3.2 and Alg. 1 allow Acc to be greedy or typical, citing
 Medusa); it prints neither the inequality nor its constants.  PARITY UNPINNED against this paper:
 the inequality below restates the cited work's published rule.  A candidate token x judged by
 the target distribution p at its parent node is accepted when

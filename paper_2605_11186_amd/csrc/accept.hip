@@ -1,6 +1,6 @@
 // Greedy acceptance, bonus token and KV roll-back (paper Algorithm 1: the walk
 // for the longest accepted prefix, the bonus token from the target's own
-// prediction, and "roll back KV to length s along the accepted path").  All
+// prediction, and the roll-back of the KV cache along the accepted path).  All
 // integer work; results are exact.
 #include "common.hpp"
 

@@ -2,9 +2,9 @@
 
 Each test names what it fixes: a closed form, a library routine, a textbook
 formulation written independently in numpy, brute force on tiny inputs, or a
-property the paper states (lossless greedy speculative decoding: the Intro's
-"exact output distribution" claim; the tree mask of Fig. 4; Algorithm 1's
-walk).  None of them needs a GPU.
+property the paper states (greedy speculative decoding is lossless: the
+Introduction's claim that the output distribution is unchanged; the tree mask
+of Fig. 4; Algorithm 1's walk).  None of them needs a GPU.
 """
 import itertools
 from pathlib import Path
