@@ -253,7 +253,7 @@ void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipS
 // as long as the longest range: ceil(items / n) item times.  The product is bound by memory
 // bandwidth, so what counts is how much of n * ceil(items / n) is real work, not how many
 // compute units are busy (measured: 224 instead of 256 busy units cost 2 %).  n is therefore
-// the count in [7/8 target, target] with the fewest item slots, idle units priced in.  7B down
+// the count in [3/4 target, target] with the fewest item slots, idle units priced in.  7B down
 // projection: 1376 items, 256 workgroups would run 6 items each with 10 % of the slots empty;
 // 230 workgroups run 5.98.
 GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn) {
@@ -272,7 +272,7 @@ GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn) {
     };
     int best = target_wgs;
     double best_cost = cost(target_wgs);
-    for (int n = target_wgs - 1; n >= target_wgs - target_wgs / 8 && n >= 1; --n) {
+    for (int n = target_wgs - 1; n >= target_wgs - target_wgs / 4 && n >= 1; --n) {
         const double c = cost(n);
         if (c < best_cost) {
             best_cost = c;
