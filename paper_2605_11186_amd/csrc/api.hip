@@ -86,23 +86,16 @@ int target_wgs() {
 // Weight rows per GEMM tile.  256-row tiles halve the re-reads of X, 128-row tiles halve the
 // number of partial tiles.  Measured back to back on one device (7B shapes): at T = 63, 128
 // rows for every product 5.10 ms per step, for the O projection only 5.155 ms, 256 rows
-// everywhere 5.09 ms.  Above 96 rows the kernel runs two groups of four waves over 128-row
-// tiles (each group accumulates two of the four X blocks: T = 128 takes 7.25 ms against 7.70 ms
-// with four accumulator blocks per wave in a 256-thread workgroup and 8.4 ms in a 512-thread
-// one, which spills), so 128 is the only choice there; for
-// 65..96 rows three accumulator blocks per wave on 256-row tiles are faster (6.2 vs 6.7 ms).
-// CATS_GEMM_BN = 128 selects the small tiles for T <= 64 too (experiments).
+// everywhere 5.09 ms.  Every tree size runs on 256-row tiles, one 32-row accumulator block per
+// wave for every 32 rows of T (at T = 128: 7.24 ms per step against 7.74 ms with two groups of
+// four waves on 128-row tiles, each accumulating two of the four blocks).
+// CATS_GEMM_BN = 128 selects the small tiles for T <= 64 (experiments).
 int gemm_bn(int rows) {
     static const int forced = [] {
         const char* e = std::getenv("CATS_GEMM_BN");
         return (e && std::atoi(e) == 128) ? 128 : 0;
     }();
-    static const int split_above = [] {   // experiments: CATS_GEMM_SPLIT_ABOVE = 64 splits from 65 rows on
-        const char* e = std::getenv("CATS_GEMM_SPLIT_ABOVE");
-        return (e && std::atoi(e) == 64) ? 64 : 96;
-    }();
-    if (rows > split_above || (forced && rows <= 64)) return 128;
-    return 256;
+    return (forced && rows <= 64) ? 128 : 256;
 }
 
 int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {

@@ -33,26 +33,21 @@ __device__ __forceinline__ void lds_barrier() {
 // and k = 8*(l/32)..+7; for B, column l%32 and the same k; the 16 results of a
 // lane are D[8*(r/4) + 4*(l/32) + r%4][l%32].
 //
-// TB: 32-row blocks of X one wave accumulates.  NWR: waves along the weight rows (a tile has
-// 32 * NWR rows).  TS: groups of such waves along the X rows: group s takes X blocks
-// s * TB .. s * TB + TB - 1 of the same weight rows, so T <= 32 * TB * TS with no more
-// accumulators per wave than TB asks for (the groups fetch the same weight fragments; the
-// second fetch is served by the caches).  ST: ring depth.  PACKED: weights come in the packed
-// fragment order (contiguous 1 KB per wave load).
-template <int TB, int NWR, int TS, int ST, bool PACKED>
-__global__ __launch_bounds__(64 * NWR * TS) void cats_gemm_skinny_bf16(GemmArgs a) {
-    constexpr int NW = NWR * TS;
-    constexpr int THREADS = 64 * NW;
+// TB: 32-row blocks of X one wave accumulates (T <= 32 * TB).  NWR: waves along the weight
+// rows (a tile has 32 * NWR rows).  ST: ring depth.  PACKED: weights come in the packed fragment
+// order (contiguous 1 KB per wave load).
+template <int TB, int NWR, int ST, bool PACKED>
+__global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
+    constexpr int THREADS = 64 * NWR;
     constexpr int BN = 32 * NWR;
-    constexpr int TBX = TB * TS;                   // 32-row blocks of the X tile in LDS
-    constexpr int XPT = TBX * 512 / THREADS;       // u32x4 of the X tile per thread
+    constexpr int XPT = TB * 512 / THREADS;        // u32x4 of the X tile per thread
     constexpr int XROWS_PER_PASS = THREADS / 16;  // tile rows covered by one pass of the block
     constexpr int NBUF = (ST % 2 == 0) ? 2 : ST;  // LDS buffers; the index is static under unrolling
     static_assert(ST >= 2 && ST <= 3, "ring depth");
-    __shared__ u32x4 xs[NBUF][2][TBX * 32][XS_ROW];  // [.][0] high parts, [.][1] low parts
+    __shared__ u32x4 xs[NBUF][2][TB * 32][XS_ROW];  // [.][0] high parts, [.][1] low parts
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = (tid >> 6) % NWR, tb0 = (tid >> 6) / NWR * TB;   // weight-row wave, first X block
+    const int lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int wg = blockIdx.x;
     const int C = a.plan.chunks;
@@ -153,8 +148,8 @@ __global__ __launch_bounds__(64 * NWR * TS) void cats_gemm_skinny_bf16(GemmArgs 
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
             const bf16x8 b = as_bf16x8(wst[s][j]);                                                  \
             _Pragma("unroll") for (int tb = 0; tb < TB; ++tb) {                                     \
-                const bf16x8 ah = as_bf16x8(xs[buf][0][(tb0 + tb) * 32 + col][2 * j + g]);          \
-                const bf16x8 al = as_bf16x8(xs[buf][1][(tb0 + tb) * 32 + col][2 * j + g]);          \
+                const bf16x8 ah = as_bf16x8(xs[buf][0][tb * 32 + col][2 * j + g]);          \
+                const bf16x8 al = as_bf16x8(xs[buf][1][tb * 32 + col][2 * j + g]);          \
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc[tb], 0, 0, 0);         \
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc[tb], 0, 0, 0);         \
             }                                                                                       \
@@ -163,10 +158,15 @@ __global__ __launch_bounds__(64 * NWR * TS) void cats_gemm_skinny_bf16(GemmArgs 
             const int n = tile * BN + wave * 32 + col;                                              \
             if (n < a.N && n % a.seg_pad < a.seg_rows) {                                            \
                 const int piece = wg - plan_first_wg(a.plan, tile);                                 \
+                /* The row offsets below are loop-invariant; computed ahead of the loop they     */ \
+                /* would occupy two registers per store for the whole kernel.  Passing the lane  */ \
+                /* term through an empty asm ties them to this block.                            */ \
+                int g_here = g;                                                                     \
+                asm volatile("" : "+v"(g_here));                                                    \
                 float* out = a.part + static_cast<size_t>(piece) * a.T * a.N + n;                   \
                 _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                   \
                     _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                \
-                    const int t = (tb0 + tb) * 32 + 8 * (r >> 2) + 4 * g + (r & 3);                 \
+                    const int t = tb * 32 + 8 * (r >> 2) + 4 * g_here + (r & 3);            \
                     if (t < a.T) out[static_cast<size_t>(t) * a.N] = acc[tb][r];                    \
                 }                                                                                   \
             }                                                                                       \
@@ -296,35 +296,33 @@ int gemm_plan_max_pieces(const GemmPlan& p) {
 // With events given, they are attached to the dispatch itself (kernel begin / end
 // timestamps), so the elapsed time is the kernel's execution time without launch latency.
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // T <= 96: one group of 8 (or 4) waves with up to three X blocks each; above: 128-row
-    // tiles, two groups of 4 waves, each accumulating two of the four X blocks (the plan's tile
-    // height says which: see the caller)
+    // one 32-row block of X per 32 rows of T; 8 waves on 256-row tiles (4 on the 128-row tiles
+    // kept for experiments, T <= 64 only)
     const int tb = (a.T + 31) / 32;
-    const bool split = tb > 3 || (tb == 3 && a.plan.bn == 128);
     const int nwr = a.plan.bn / 32;
-    const dim3 grid(a.plan.n_wgs), block(64 * nwr * (split ? 2 : 1));
-#define CATS_LAUNCH_V(TBV, NWRV, TSV)                                                                   \
+    const dim3 grid(a.plan.n_wgs), block(64 * nwr);
+#define CATS_LAUNCH_V(TBV, NWRV)                                                                        \
     if (a.packed)                                                                                       \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, TSV, GEMM_ST, true>), grid, block, 0, st, \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, (TBV <= 2 ? GEMM_ST : 2), true>), grid, block, 0, st,    \
                               ev_start, ev_stop, 0, a);                                                 \
     else                                                                                                \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, TSV, GEMM_ST, false>), grid, block, 0, st, \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, (TBV <= 2 ? GEMM_ST : 2), false>), grid, block, 0, st,   \
                               ev_start, ev_stop, 0, a)
-    if (split) {
-        CATS_LAUNCH_V(2, 4, 2);
-    } else if (nwr == 4) {
+    if (nwr == 4) {
         if (tb == 1) {
-            CATS_LAUNCH_V(1, 4, 1);
+            CATS_LAUNCH_V(1, 4);
         } else {
-            CATS_LAUNCH_V(2, 4, 1);
+            CATS_LAUNCH_V(2, 4);
         }
     } else {
         if (tb == 1) {
-            CATS_LAUNCH_V(1, 8, 1);
+            CATS_LAUNCH_V(1, 8);
         } else if (tb == 2) {
-            CATS_LAUNCH_V(2, 8, 1);
+            CATS_LAUNCH_V(2, 8);
+        } else if (tb == 3) {
+            CATS_LAUNCH_V(3, 8);
         } else {
-            CATS_LAUNCH_V(3, 8, 1);
+            CATS_LAUNCH_V(4, 8);
         }
     }
 #undef CATS_LAUNCH_V
