@@ -90,7 +90,25 @@ int target_wgs() {
 // wave for every 32 rows of T (at T = 128: 7.24 ms per step against 7.74 ms with two groups of
 // four waves on 128-row tiles, each accumulating two of the four blocks).
 // CATS_GEMM_BN = 128 selects the small tiles for T <= 64 (experiments).
+// k values per work item.  Up to 32 rows, two groups of four waves share a 128-row tile, each
+// multiplying one 128-wide half of a 256-wide item, and add their sums through LDS when the tile
+// ends: the same bytes in flight as with eight waves on 256 rows, but half the bytes of partial
+// sums to write here and to read back in the consumer, paid for with twice the X bytes staged
+// per weight byte.  Measured on one device (7B shapes, per step): T = 1 -2.7 %, T = 8 -3.7 %,
+// T = 16 / 24 -4.3 %, T = 32 -5.2 %; with two accumulator blocks per wave (T = 48, 63) the
+// staging costs more than the partial sums save (+0.7 %).  CATS_GEMM_KG = 1 switches it off,
+// = 2 extends it to 64 rows (experiments).
+int gemm_kc(int rows) {
+    static const int mode = [] {
+        const char* e = std::getenv("CATS_GEMM_KG");
+        return e ? std::atoi(e) : 0;
+    }();
+    const int limit = mode == 1 ? 0 : (mode == 2 ? 64 : 32);
+    return rows <= limit ? 2 * GEMM_KC : GEMM_KC;
+}
+
 int gemm_bn(int rows) {
+    if (gemm_kc(rows) == 2 * GEMM_KC) return 128;
     static const int forced = [] {
         const char* e = std::getenv("CATS_GEMM_BN");
         return (e && std::atoi(e) == 128) ? 128 : 0;
@@ -160,7 +178,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.N = n_seg * g.seg_pad;
     g.K = K;
     g.T = c->rows;
-    g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn(g.T));
+    g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn(g.T), gemm_kc(g.T));
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
@@ -387,8 +405,11 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
                               {d.hidden, d.ffn}, {pad32(d.vocab), d.hidden}};
     for (auto& s : shapes)
         for (int bn : {128, 256})
-            part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
-                                                make_gemm_plan(s[0], s[1], target_wgs(), bn))) * s[0]);
+            for (int kc : {GEMM_KC, 2 * GEMM_KC}) {
+                if (kc != GEMM_KC && bn != 128) continue;
+                part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
+                                                    make_gemm_plan(s[0], s[1], target_wgs(), bn, kc))) * s[0]);
+            }
     c->part_elems = part_cols * Tm;
     c->attn_max_chunks = 32;
     const size_t t_pad = (Tm + 31) / 32 * 32;
@@ -513,7 +534,7 @@ int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden,
     rn.embed = nullptr;
     rn.token = nullptr;
     rn.part = nullptr;
-    rn.plan = GemmPlan{1, 1, 1, 1};
+    rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(w->g_attn);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
@@ -566,7 +587,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, int32_t n_rows, cons
     rn.embed = nullptr;
     rn.token = nullptr;
     rn.part = nullptr;
-    rn.plan = GemmPlan{1, 1, 1, 1};
+    rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(g_final);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
@@ -593,7 +614,7 @@ static void enqueue_rows_and_layers(cats_ctx* ctx, const cats_layer_weights* lay
     rn.embed = static_cast<const bf16_t*>(embed);
     rn.token = ctx->token + ctx->n0;
     rn.part = nullptr;
-    rn.plan = GemmPlan{1, 1, 1, 1};
+    rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
     rn.gain = static_cast<const bf16_t*>(layer_end > layer_begin ? layers[layer_begin].g_attn : last_gain);
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;
@@ -850,7 +871,7 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
     rn.embed = static_cast<const bf16_t*>(embed);
     rn.token = ctx->token;
     rn.part = nullptr;
-    rn.plan = GemmPlan{1, 1, 1, 1};
+    rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
     rn.gain = nullptr;  // input rows only; each layer's first norm is launched once its gains have arrived
     rn.xn = ctx->xn;
     rn.xn_lo = ctx->xn_lo;

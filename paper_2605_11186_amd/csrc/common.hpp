@@ -42,7 +42,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast
 // workgroup - first workgroup of that tile.  Consumers add the pieces in index order.
 struct GemmPlan {
     int bn;      // weight rows per tile
-    int chunks;  // K chunks per tile
+    int kc;      // k values per work item (128 or 256)
+    int chunks;  // work items (K chunks of kc values) per tile
     int n_wgs;   // workgroups
     int items;   // tiles * chunks
 };
@@ -87,7 +88,7 @@ size_t packed_matrix_elems(int rows, int cols);
 constexpr int GEMM_BN = CATS_GEMM_BN;    // weight rows per workgroup (32 per wave)
 constexpr int GEMM_KC = 128;             // k elements per pipeline stage
 constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
-GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn);   // bn: 256 or 128 weight rows per tile
+GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc = GEMM_KC);   // bn: 256 or 128 weight rows per tile; kc: 128, or 256 with bn 128
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 

@@ -19,7 +19,6 @@
 
 namespace {
 
-constexpr int XS_ROW = GEMM_KC / 8 + 1;  // u32x4 per staged row: 256 B of data + 16 B pad
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait
 // for every outstanding global load (vmcnt(0)), i.e. drain the prefetch ring.
@@ -34,28 +33,36 @@ __device__ __forceinline__ void lds_barrier() {
 // lane are D[8*(r/4) + 4*(l/32) + r%4][l%32].
 //
 // TB: 32-row blocks of X one wave accumulates (T <= 32 * TB).  NWR: waves along the weight
-// rows (a tile has 32 * NWR rows).  ST: ring depth.  PACKED: weights come in the packed fragment
-// order (contiguous 1 KB per wave load).
-template <int TB, int NWR, int ST, bool PACKED>
-__global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
-    constexpr int THREADS = 64 * NWR;
+// rows (a tile has 32 * NWR rows).  KG: groups of such waves along k: an item then spans KG
+// chunks of 128 k-values, group kg multiplies chunk kg of it for the same weight rows, and the
+// groups' sums are added through LDS when a tile (or the workgroup's range) ends, so that a
+// partial tile is 32 * NWR rows high whatever the number of waves.  ST: ring depth.  PACKED:
+// weights come in the packed fragment order (contiguous 1 KB per wave load).
+template <int TB, int NWR, int KG, int ST, bool PACKED>
+__global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs a) {
+    constexpr int THREADS = 64 * NWR * KG;
     constexpr int BN = 32 * NWR;
-    constexpr int XPT = TB * 512 / THREADS;        // u32x4 of the X tile per thread
-    constexpr int XROWS_PER_PASS = THREADS / 16;  // tile rows covered by one pass of the block
+    constexpr int KC = GEMM_KC * KG;               // k elements per item
+    constexpr int XCOLS = KC / 8;                  // 16-byte columns of a staged row
+    constexpr int XS_ROW = XCOLS + 1;              // u32x4 per staged row: data + 16 B pad
+    constexpr int XPT = TB * 32 * XCOLS / THREADS;      // u32x4 of the X tile per thread
+    constexpr int XROWS_PER_PASS = THREADS / XCOLS;     // tile rows covered by one pass of the block
     constexpr int NBUF = (ST % 2 == 0) ? 2 : ST;  // LDS buffers; the index is static under unrolling
     static_assert(ST >= 2 && ST <= 3, "ring depth");
     __shared__ u32x4 xs[NBUF][2][TB * 32][XS_ROW];  // [.][0] high parts, [.][1] low parts
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = (tid >> 6) % NWR, kg = (tid >> 6) / NWR;
     const int col = lane & 31, g = lane >> 5;
     const int wg = blockIdx.x;
     const int C = a.plan.chunks;
+    const int C128 = (a.K + GEMM_KC - 1) / GEMM_KC;
+    (void)C128;
     const int item_lo = plan_item_begin(a.plan, wg);
     const int n_items = plan_item_begin(a.plan, wg + 1) - item_lo;
 
     // staging assignment: thread -> (row, 16-byte column) of the X tile
-    const int xr = tid >> 4, xc = tid & 15;
+    const int xr = tid / XCOLS, xc = tid % XCOLS;
 
     u32x4 wst[ST][8];
     u32x4 xst[2 * XPT];  // X of the next item only: it comes from L2, one step ahead is enough
@@ -84,7 +91,7 @@ __global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
 #define CATS_ITEM(i, tile_, k0_)                  \
     const int gi_ = item_lo + (i);                \
     const int tile_ = gi_ / C;                    \
-    const int k0_ = (gi_ - tile_ * C) * GEMM_KC;
+    const int k0_ = (gi_ - tile_ * C) * KC;
 
 #define CATS_LOAD_X(i)                                                                              \
     {                                                                                               \
@@ -111,7 +118,8 @@ __global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
             const int lrb_ = min((lt_ * BN + wave * 32) / PACK_ROWS, n_rb_total - 1);               \
             const int lseg_ = lrb_ / rb_per_seg;                                                    \
             lw_ = (lseg_ == 0 ? a.w[0] : (lseg_ == 1 ? a.w[1] : a.w[2])) +                          \
-                  (static_cast<size_t>(lrb_ - lseg_ * rb_per_seg) * C + lk_ / GEMM_KC) * (8 * PACK_FRAG) + lane * 8; \
+                  (static_cast<size_t>(lrb_ - lseg_ * rb_per_seg) * C128 + min(lk_ / GEMM_KC + kg, C128 - 1)) * \
+                      (8 * PACK_FRAG) + lane * 8;                                                   \
         } else {                                                                                    \
             const int lv_ = min(lt_ * BN + wave * 32 + col, a.N - 1);                               \
             const int lseg_ = lv_ / a.seg_pad;                                                      \
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
         }                                                                                           \
         _Pragma("unroll") for (int j = 0; j < 8; ++j)                                               \
             wst[slot][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(               \
-                PACKED ? lw_ + j * PACK_FRAG : lw_ + min(lk_ + 16 * j, k_last_w)));                 \
+                PACKED ? lw_ + j * PACK_FRAG : lw_ + min(lk_ + GEMM_KC * kg + 16 * j, k_last_w)));  \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
@@ -148,15 +156,30 @@ __global__ __launch_bounds__(64 * NWR) void cats_gemm_skinny_bf16(GemmArgs a) {
         _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                             \
             const bf16x8 b = as_bf16x8(wst[s][j]);                                                  \
             _Pragma("unroll") for (int tb = 0; tb < TB; ++tb) {                                     \
-                const bf16x8 ah = as_bf16x8(xs[buf][0][tb * 32 + col][2 * j + g]);          \
-                const bf16x8 al = as_bf16x8(xs[buf][1][tb * 32 + col][2 * j + g]);          \
+                const bf16x8 ah = as_bf16x8(xs[buf][0][tb * 32 + col][16 * kg + 2 * j + g]); \
+                const bf16x8 al = as_bf16x8(xs[buf][1][tb * 32 + col][16 * kg + 2 * j + g]); \
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc[tb], 0, 0, 0);         \
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc[tb], 0, 0, 0);         \
             }                                                                                       \
         }                                                                                           \
-        if (k0 + GEMM_KC >= a.K || (i) == n_items - 1) {                                            \
+        if (k0 + KC >= a.K || (i) == n_items - 1) {                                                 \
+            if (KG > 1) { /* add the k groups: the other LDS buffer is idle at this point */        \
+                float* red = reinterpret_cast<float*>(&xs[(buf + 1) % NBUF][0][0][0]);              \
+                if (kg > 0) {                                                                       \
+                    _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                               \
+                        _Pragma("unroll") for (int r = 0; r < 16; ++r)                              \
+                            red[((wave * TB + tb) * 16 + r) * 64 + lane] = acc[tb][r];              \
+                }                                                                                   \
+                lds_barrier();                                                                      \
+                if (kg == 0) {                                                                      \
+                    _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                               \
+                        _Pragma("unroll") for (int r = 0; r < 16; ++r)                              \
+                            acc[tb][r] += red[((wave * TB + tb) * 16 + r) * 64 + lane];             \
+                }                                                                                   \
+                lds_barrier(); /* the buffer is staged again in the next step */                   \
+            }                                                                                       \
             const int n = tile * BN + wave * 32 + col;                                              \
-            if (n < a.N && n % a.seg_pad < a.seg_rows) {                                            \
+            if (kg == 0 && n < a.N && n % a.seg_pad < a.seg_rows) {                                 \
                 const int piece = wg - plan_first_wg(a.plan, tile);                                 \
                 /* The row offsets below are loop-invariant; computed ahead of the loop they     */ \
                 /* would occupy two registers per store for the whole kernel.  Passing the lane  */ \
@@ -256,10 +279,11 @@ void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipS
 // the count in [3/4 target, target] with the fewest item slots, idle units priced in.  7B down
 // projection: 1376 items, 256 workgroups would run 6 items each with 10 % of the slots empty;
 // 230 workgroups run 5.98.
-GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn) {
+GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc) {
     GemmPlan p;
     p.bn = bn;
-    p.chunks = (K + GEMM_KC - 1) / GEMM_KC;
+    p.kc = kc;
+    p.chunks = (K + kc - 1) / kc;
     const int tiles = (N + bn - 1) / bn;
     p.items = tiles * p.chunks;
     if (target_wgs >= p.items) {
@@ -296,33 +320,39 @@ int gemm_plan_max_pieces(const GemmPlan& p) {
 // With events given, they are attached to the dispatch itself (kernel begin / end
 // timestamps), so the elapsed time is the kernel's execution time without launch latency.
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    // one 32-row block of X per 32 rows of T; 8 waves on 256-row tiles (4 on the 128-row tiles
-    // kept for experiments, T <= 64 only)
+    // one 32-row block of X per 32 rows of T; 8 waves: on 256-row tiles, or as two k groups on
+    // 128-row tiles (the plan says which); 4 waves on 128-row tiles are kept for experiments
     const int tb = (a.T + 31) / 32;
-    const int nwr = a.plan.bn / 32;
-    const dim3 grid(a.plan.n_wgs), block(64 * nwr);
-#define CATS_LAUNCH_V(TBV, NWRV)                                                                        \
+    const int nwr = a.plan.bn / 32, kgs = a.plan.kc / GEMM_KC;
+    const dim3 grid(a.plan.n_wgs), block(64 * nwr * kgs);
+#define CATS_LAUNCH_V(TBV, NWRV, KGV)                                                                   \
     if (a.packed)                                                                                       \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, (TBV <= 2 ? GEMM_ST : 2), true>), grid, block, 0, st,    \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, (TBV <= 2 ? GEMM_ST : 2), true>), grid, block, 0, st,    \
                               ev_start, ev_stop, 0, a);                                                 \
     else                                                                                                \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, (TBV <= 2 ? GEMM_ST : 2), false>), grid, block, 0, st,   \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, (TBV <= 2 ? GEMM_ST : 2), false>), grid, block, 0, st,   \
                               ev_start, ev_stop, 0, a)
-    if (nwr == 4) {
+    if (nwr == 4 && kgs == 2) {
         if (tb == 1) {
-            CATS_LAUNCH_V(1, 4);
+            CATS_LAUNCH_V(1, 4, 2);
         } else {
-            CATS_LAUNCH_V(2, 4);
+            CATS_LAUNCH_V(2, 4, 2);
+        }
+    } else if (nwr == 4) {
+        if (tb == 1) {
+            CATS_LAUNCH_V(1, 4, 1);
+        } else {
+            CATS_LAUNCH_V(2, 4, 1);
         }
     } else {
         if (tb == 1) {
-            CATS_LAUNCH_V(1, 8);
+            CATS_LAUNCH_V(1, 8, 1);
         } else if (tb == 2) {
-            CATS_LAUNCH_V(2, 8);
+            CATS_LAUNCH_V(2, 8, 1);
         } else if (tb == 3) {
-            CATS_LAUNCH_V(3, 8);
+            CATS_LAUNCH_V(3, 8, 1);
         } else {
-            CATS_LAUNCH_V(4, 8);
+            CATS_LAUNCH_V(4, 8, 1);
         }
     }
 #undef CATS_LAUNCH_V

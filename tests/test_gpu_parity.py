@@ -101,6 +101,31 @@ def test_verify_tree_tiny_prefilled_context(tiny, name, parent, depth):
     check_step(tiny, kc, vc, ks, vs, 128, tok, parent, depth)
 
 
+# Hidden 384 = 3 and FFN 1104 = 8.6 chunks of 128 k-values: an odd chunk count (the second k group
+# of the last 256-wide item has nothing to multiply), a ragged last chunk, and a vocabulary that
+# ends inside a tile.
+ODD = synth.ModelDims(2, 384, 6, 64, 1104, 1000)
+
+
+@pytest.fixture(scope="module", params=[False, True], ids=["rowmajor", "packed"])
+def odd(request):
+    p = Pair(ODD, SEED + 5, max_ctx=192, max_tree=128, packed=request.param)
+    yield p
+    p.close()
+
+
+@pytest.mark.parametrize("T", [9, 31, 40, 70, 100, 128])
+def test_odd_chunk_counts_every_accumulator_depth(odd, T):
+    """One to four accumulator blocks per wave (and the two-k-group variant up to 32 rows) on
+    shapes whose k range does not divide into whole items."""
+    S = 37
+    parent, depth = synth.random_tree(T, 8, T)
+    tok = synth.distinct_sibling_tokens(parent, ODD.vocab, T)
+    kc, vc = odd.oracle_cache_random(SEED + T, S)
+    ks, vs = odd.device_cache_from_oracle(kc, vc, S)
+    check_step(odd, kc, vc, ks, vs, S, tok, parent, depth)
+
+
 @pytest.mark.parametrize("S", [0, 1, 31, 32, 33, 100, 191])
 def test_verify_tree_ragged_context_lengths(tiny, S):
     parent, depth = synth.random_tree(45, 6, S + 1)
