@@ -201,7 +201,7 @@ def main():
     ap.add_argument("--ctx", type=int, default=0, help="override the KV context length")
     ap.add_argument("--seed", type=int, default=11186)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-layers", type=int, default=2)
+    ap.add_argument("--cpu-sample-layers", type=int, default=8)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -553,17 +553,26 @@ def main():
         for l in range(n_keep):
             kc[l, :S] = synth.f32_from_bf16_bits(host_kv[l][0])
             vc[l, :S] = synth.f32_from_bf16_bits(host_kv[l][1])
-        t1 = time.perf_counter()
-        x = orc.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=n_keep)
-        t_layers = time.perf_counter() - t1
-        t1 = time.perf_counter()
-        orc.lm_head(x)
-        t_lm = time.perf_counter() - t1
+        # the sampled layers and the LM head are run again and again until about ten seconds of
+        # CPU work have been spent (at most 12 passes); the median pass is reported
+        passes, spent = [], 0.0
+        while len(passes) < 12 and (spent < 10.0 or len(passes) < 3):
+            t1 = time.perf_counter()
+            x = orc.tree_forward(kc, vc, S, parent, depth, tokens=tok, layer_end=n_keep)
+            t_layers = time.perf_counter() - t1
+            t1 = time.perf_counter()
+            orc.lm_head(x)
+            t_lm = time.perf_counter() - t1
+            passes.append((t_layers, t_lm))
+            spent += t_layers + t_lm
+        t_layers = float(np.median([p[0] for p in passes]))
+        t_lm = float(np.median([p[1] for p in passes]))
         est = t_layers * L / n_keep + t_lm
         out["cpu_baseline"] = {
             "value": round(1.0 / est, 5), "unit": "steps/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"float32 oracle, same tree and context: layers 0..{n_keep - 1} of {L} timed "
-                      f"({t_layers:.2f} s) and scaled by {L}/{n_keep}, plus the full LM head ({t_lm:.2f} s)",
+            "sample": f"float32 oracle, same tree and context: layers 0..{n_keep - 1} of {L} "
+                      f"({t_layers:.2f} s, scaled by {L}/{n_keep}) plus the full LM head ({t_lm:.2f} s); "
+                      f"median of {len(passes)} passes, {spent:.1f} s of CPU work in all",
             "est_s_per_step": round(est, 2)}
 
     cats.cats_destroy(ctx)
