@@ -24,8 +24,10 @@
  *    NULL = default stream) and the call returns without waiting, except where
  *    a HOST output pointer is given (then the call synchronises the stream).
  *  - Every function returns CATS_OK (0) or a negative cats_status.  Arguments are
- *    validated on the host before anything is enqueued; a call that fails has
- *    enqueued nothing.
+ *    validated on the host before anything is enqueued: a call that returns
+ *    CATS_EINVAL, CATS_ECAPACITY or CATS_ESTATE has enqueued nothing.  CATS_EHIP
+ *    reports a HIP runtime failure, which may surface after part of the call's
+ *    work was enqueued; the outputs of such a call are undefined.
  *  - Calls that use one cats_ctx must not overlap in time (they share scratch).
  */
 #ifndef CATS_H

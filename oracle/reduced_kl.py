@@ -1,7 +1,7 @@
 """CPU oracle of the Reduced KL Loss (Section 3.3, Eq. 2; Appendix B, steps 1-3).
 
-TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
-benchmark's CPU-baseline leg.  The GPU library never imports or calls this.
+TEST INFRASTRUCTURE ONLY: imported by the tests and by the benchmark's CPU-baseline
+leg of the loss workload.  The GPU library never imports or calls this.
 
 Plain numpy in float64, the three steps of the appendix in their order and
 notation.  Inputs are logits; p_target and q_draft are their softmaxes.

@@ -2,7 +2,6 @@
 // in which one verify step's kernels are enqueued (paper Algorithm 1, Stage 3
 // through the commit step).
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -13,6 +12,7 @@ constexpr int CATS_PROF_MAX = 1024;  // GEMM launches that can be timed between 
 struct cats_ctx {
     cats_model_desc d;
     int device;
+    int n_cus;   // compute units of that device
     // uploaded tree (device) and its host copy
     int32_t *token, *parent, *depth;
     u32x4* anc;  // [max_tree] ancestor-or-self masks of the uploaded tree
@@ -72,62 +72,31 @@ inline int hip_fail(hipError_t e) {
 
 inline size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
 
-// Workgroups per GEMM launch: one per CU (the GEMM kernel's register footprint lets one
-// 512-thread workgroup live on a CU).  CATS_GEMM_WGS overrides it.
-int target_wgs() {
-    static int v = [] {
-        const char* e = std::getenv("CATS_GEMM_WGS");
-        const int n = e ? std::atoi(e) : 0;
-        return n > 0 ? n : 256;
-    }();
-    return v;
-}
+// Workgroups per GEMM launch: one per compute unit of the context's device (the GEMM kernel's
+// register footprint lets one 512-thread workgroup live on a CU); cats_create reads the count.
+int target_wgs(const cats_ctx* c) { return c->n_cus; }
 
-// Weight rows per GEMM tile.  256-row tiles halve the re-reads of X, 128-row tiles halve the
-// number of partial tiles.  Measured back to back on one device (7B shapes): at T = 63, 128
-// rows for every product 5.10 ms per step, for the O projection only 5.155 ms, 256 rows
-// everywhere 5.09 ms.  Every tree size runs on 256-row tiles, one 32-row accumulator block per
-// wave for every 32 rows of T (at T = 128: 7.24 ms per step against 7.74 ms with two groups of
-// four waves on 128-row tiles, each accumulating two of the four blocks).
-// CATS_GEMM_BN = 128 selects the small tiles for T <= 64 (experiments).
-// k values per work item.  Up to 32 rows, two groups of four waves share a 128-row tile, each
-// multiplying one 128-wide half of a 256-wide item, and add their sums through LDS when the tile
-// ends: the same bytes in flight as with eight waves on 256 rows, but half the bytes of partial
-// sums to write here and to read back in the consumer, paid for with twice the X bytes staged
-// per weight byte.  Measured on one device (7B shapes, per step): T = 1 -2.7 %, T = 8 -3.7 %,
-// T = 16 / 24 -4.3 %, T = 32 -5.2 %; with two accumulator blocks per wave (T = 48, 63) the
-// staging costs more than the partial sums save (+0.7 %).  CATS_GEMM_KG = 1 switches it off,
-// = 2 extends it to 64 rows (experiments).
-int gemm_kc(int rows) {
-    static const int mode = [] {
-        const char* e = std::getenv("CATS_GEMM_KG");
-        return e ? std::atoi(e) : 0;
-    }();
-    const int limit = mode == 1 ? 0 : (mode == 2 ? 64 : 32);
-    return rows <= limit ? 2 * GEMM_KC : GEMM_KC;
-}
+// k values per work item and weight rows per tile.  Up to 32 rows, two groups of four waves share
+// a 128-row tile, each multiplying one 128-wide half of a 256-wide item, and add their sums
+// through LDS when the tile ends: the same bytes in flight as with eight waves on 256 rows, but
+// half the bytes of partial sums to write here and to read back in the consumer, paid for with
+// twice the X bytes staged per weight byte.  Measured on one device (7B shapes, per step):
+// T = 1 -2.7 %, T = 8 -3.7 %, T = 16 / 24 -4.3 %, T = 32 -5.2 %; with two accumulator blocks per
+// wave (T = 48, 63) the staging costs more than the partial sums save (+0.7 %).  Larger trees
+// run on 256-row tiles, one 32-row accumulator block per wave for every 32 rows of T (256-row
+// tiles halve the re-reads of X, 128-row tiles halve the number of partial tiles; at T = 63,
+// 128 rows for every product 5.10 ms per step against 5.09 ms).
+int gemm_kc(int rows) { return rows <= 32 ? 2 * GEMM_KC : GEMM_KC; }
+int gemm_bn(int rows) { return rows <= 32 ? 128 : 256; }
 
-int gemm_bn(int rows) {
-    if (gemm_kc(rows) == 2 * GEMM_KC) return 128;
-    static const int forced = [] {
-        const char* e = std::getenv("CATS_GEMM_BN");
-        return (e && std::atoi(e) == 128) ? 128 : 0;
-    }();
-    return (forced && rows <= 64) ? 128 : 256;
-}
-
-int attn_blocks_per_chunk(const cats_ctx* c, int n_keys) {
+// Key blocks per attention chunk: aim at one wave per SIMD (four SIMDs per compute unit; the
+// kernel needs most of the register file): heads * chunks * query groups * waves per workgroup.
+int attn_blocks_per_chunk(int rows, int n_heads, int max_chunks, int n_cus, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    // aim at one wave per SIMD (1024 SIMDs; the kernel needs most of the register file):
-    // heads * chunks * query groups * waves per workgroup
-    const int tq = (c->rows + 31) / 32;
-    static const int wave_target = [] {
-        const char* e = std::getenv("CATS_ATTN_WAVES");
-        const int v = e ? std::atoi(e) : 0;
-        return v > 0 ? v : 1024;
-    }();
-    int chunks = std::max(1, wave_target / std::max(1, c->d.n_heads * tq * ATTN_WAVES));
-    chunks = std::min(chunks, std::min(n_blocks, c->attn_max_chunks));
+    const int tq = (rows + 31) / 32;
+    const int wave_target = 4 * n_cus;
+    int chunks = std::max(1, wave_target / std::max(1, n_heads * tq * ATTN_WAVES));
+    chunks = std::min(chunks, std::min(n_blocks, max_chunks));
     return (n_blocks + chunks - 1) / chunks;
 }
 
@@ -178,7 +147,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.N = n_seg * g.seg_pad;
     g.K = K;
     g.T = c->rows;
-    g.plan = make_gemm_plan(g.N, K, target_wgs(), gemm_bn(g.T), gemm_kc(g.T));
+    g.plan = make_gemm_plan(g.N, K, target_wgs(c), gemm_bn(g.T), gemm_kc(g.T));
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
@@ -208,7 +177,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.max_ctx = c->d.max_ctx;
     a.ctx_len = ctx_len;
     const int n_keys = ctx_len + c->T;
-    a.blocks_per_chunk = attn_blocks_per_chunk(c, n_keys);
+    a.blocks_per_chunk = attn_blocks_per_chunk(c->rows, c->d.n_heads, c->attn_max_chunks, c->n_cus, n_keys);
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
     a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
     a.t_pad = (a.Tq + 31) / 32 * 32;
@@ -393,7 +362,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->prof_on = false;
     c->prof_n = 0;
     for (auto& e : c->prof_ev) e = nullptr;
-    if (hipGetDevice(&c->device) != hipSuccess) {
+    if (hipGetDevice(&c->device) != hipSuccess ||
+        hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess ||
+        c->n_cus < 1) {
         delete c;
         return hip_fail(hipGetLastError());
     }
@@ -408,7 +379,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
             for (int kc : {GEMM_KC, 2 * GEMM_KC}) {
                 if (kc != GEMM_KC && bn != 128) continue;
                 part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
-                                                    make_gemm_plan(s[0], s[1], target_wgs(), bn, kc))) * s[0]);
+                                                    make_gemm_plan(s[0], s[1], target_wgs(c), bn, kc))) * s[0]);
             }
     c->part_elems = part_cols * Tm;
     c->attn_max_chunks = 32;
@@ -440,7 +411,10 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
         delete c;
         return hip_fail(e);
     }
+    // The zeros (arrival counters, unused sum-of-squares slots) must be in place before a first
+    // call on any stream, also one that does not synchronise with the null stream: wait here once.
     e = hipMemset(c->flat, 0, off);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e != hipSuccess) {
         (void)hipFree(c->flat);
         delete c;

@@ -79,15 +79,8 @@ constexpr int PACK_ROWS = 32;   // rows per packed row block
 constexpr int PACK_FRAG = 512;  // bf16 elements per packed 1 KB fragment
 void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipStream_t st);
 size_t packed_matrix_elems(int rows, int cols);
-#ifndef CATS_GEMM_BN
-#define CATS_GEMM_BN 256
-#endif
-#ifndef CATS_GEMM_ST
-#define CATS_GEMM_ST 2
-#endif
-constexpr int GEMM_BN = CATS_GEMM_BN;    // weight rows per workgroup (32 per wave)
 constexpr int GEMM_KC = 128;             // k elements per pipeline stage
-constexpr int GEMM_ST = CATS_GEMM_ST;    // register ring depth for T <= 64
+constexpr int GEMM_ST = 2;               // register ring depth
 GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc = GEMM_KC);   // bn: 256 or 128 weight rows per tile; kc: 128, or 256 with bn 128
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);

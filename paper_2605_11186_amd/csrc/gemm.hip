@@ -327,10 +327,10 @@ void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEven
     const dim3 grid(a.plan.n_wgs), block(64 * nwr * kgs);
 #define CATS_LAUNCH_V(TBV, NWRV, KGV)                                                                   \
     if (a.packed)                                                                                       \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, (TBV <= 2 ? GEMM_ST : 2), true>), grid, block, 0, st,    \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, GEMM_ST, true>), grid, block, 0, st,    \
                               ev_start, ev_stop, 0, a);                                                 \
     else                                                                                                \
-        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, (TBV <= 2 ? GEMM_ST : 2), false>), grid, block, 0, st,   \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, GEMM_ST, false>), grid, block, 0, st,   \
                               ev_start, ev_stop, 0, a)
     if (nwr == 4 && kgs == 2) {
         if (tb == 1) {
