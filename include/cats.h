@@ -276,6 +276,25 @@ int cats_lm_head_argmax(cats_ctx *ctx, const float *hidden, int32_t n_rows, cons
                         const void *w_lm, float *logits_out, int32_t *argmax_out, float *margin_out,
                         void *stream);
 
+/* cats_tree_attention for callers that cannot allocate device memory or hold a cats_ctx: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as
+ * cats_set_tree + cats_tree_attention, same kernels.  Calls no hipMalloc / hipFree and no
+ * allocating library routine: the tree masks and the per-chunk partial results live in a fixed
+ * array inside the library's code object (CATS_NOALLOC_SCRATCH_BYTES, one copy per GPU, held
+ * until the process ends).  q, kv, out: DEVICE, as for cats_tree_attention; parent: HOST int32
+ * [n_nodes] in topological order (parent[0] = -1, 0 <= parent[i] < i, depth <= CATS_MAX_DEPTH),
+ * copied during the call.  The cache layout is given by n_heads, head_dim (64 or 128) and
+ * max_ctx (multiple of 64).  Only kernel launches are enqueued on `stream`.
+ * CATS_EINVAL: NULL pointer, malformed tree, bad shape.  CATS_ECAPACITY: n_nodes >
+ * CATS_MAX_TREE, ctx_len + n_nodes > max_ctx, or a shape whose partial results do not fit the
+ * fixed array (8 MiB hold every shape with n_heads * head_dim <= 8192 on a 256-CU device).
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents: calls that
+ * overlap in time on one GPU (different streams, different threads) race; order them. */
+#define CATS_NOALLOC_SCRATCH_BYTES (8u << 20)
+int cats_tree_attention_noalloc(const void *q, const cats_kv_layer *kv, const int32_t *parent,
+                                int32_t n_nodes, int32_t n_heads, int32_t head_dim, int32_t max_ctx,
+                                int32_t ctx_len, void *out, void *stream);
+
 /* Measurement aid for the weight-streaming GEMM (the layer-weight pass of the
  * "Target verification pass"): while enabled, every GEMM launch made through
  * this context carries a pair of HIP events attached to its dispatch on its own

@@ -13,7 +13,8 @@ import numpy as np
 
 __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWeights", "KVLayer",
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
-           "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention",
+           "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention", "cats_tree_attention_noalloc",
+           "CATS_NOALLOC_SCRATCH_BYTES",
            "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_reduced_kl_loss", "cats_set_acceptance",
            "cats_typical_stats", "cats_compact_along", "CATS_LOSS_MAX_K", "CATS_LOSS_MAX_VOCAB",
            "cats_lm_head_argmax",
@@ -28,6 +29,7 @@ CATS_MAX_TREE = 128
 CATS_MAX_DEPTH = 16
 CATS_LOSS_MAX_K = 64
 CATS_LOSS_MAX_VOCAB = 36864
+CATS_NOALLOC_SCRATCH_BYTES = 8 << 20
 CATS_OK, CATS_EINVAL, CATS_ECAPACITY, CATS_ESTATE, CATS_EHIP = 0, -1, -2, -3, -4
 
 _LIB_PATH = Path(__file__).resolve().parent / "libcats.so"
@@ -102,6 +104,8 @@ _SIGNATURES = {
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_tree_attention_noalloc": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                    C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
 }
 
 
@@ -203,6 +207,15 @@ def cats_verify_layer(ctx, weights: LayerWeights, hidden, kv: KVLayer, ctx_len: 
 def cats_tree_attention(ctx, q, kv: KVLayer, ctx_len: int, out, stream=None):
     _check(library().cats_tree_attention(ctx, _dp(q), C.byref(kv), int(ctx_len), _dp(out),
                                          _stream(stream)))
+
+
+def cats_tree_attention_noalloc(q, kv: KVLayer, parent, n_heads: int, head_dim: int, max_ctx: int,
+                                ctx_len: int, out, stream=None):
+    """cats_tree_attention without a context: nothing is allocated (fixed scratch in the library)."""
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    _check(library().cats_tree_attention_noalloc(_dp(q), C.byref(kv), parent.ctypes.data, len(parent),
+                                                 int(n_heads), int(head_dim), int(max_ctx), int(ctx_len),
+                                                 _dp(out), _stream(stream)))
 
 
 def cats_accept_and_compact(ctx, node_argmax, kv_arr, layer_begin: int, layer_end: int,

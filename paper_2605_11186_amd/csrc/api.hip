@@ -3,6 +3,7 @@
 // through the commit step).
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "common.hpp"
@@ -881,13 +882,122 @@ int cats_verify_tree_streamed(cats_ctx* ctx, const cats_layer_weights* host_laye
                                   typical);
 }
 
+// ---------------------------------------------------------------- no-allocation entry point
+// Scratch of cats_tree_attention_noalloc: a fixed array in the code object, one copy per GPU,
+// held until the process ends.  In host code the name below is only a handle for
+// hipGetSymbolAddress; kernels and copies get the device address it returns.
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[CATS_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int NOALLOC_MAX_DEVICES = 64;
+struct NoallocDevice {
+    unsigned char* ptr = nullptr;   // device address of this GPU's copy of `scratch`
+    int n_cus = 0;
+};
+NoallocDevice g_noalloc[NOALLOC_MAX_DEVICES];
+std::mutex g_noalloc_mutex;
+
+// Address of the current device's scratch array, looked up once per device.
+int noalloc_device(NoallocDevice** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES) return CATS_ECAPACITY;
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    NoallocDevice& d = g_noalloc[dev];
+    if (!d.ptr) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        int n_cus = 0;
+        HIP_TRY(hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n_cus < 1) return hip_fail(hipErrorInvalidDevice);
+        d.n_cus = n_cus;
+        d.ptr = static_cast<unsigned char*>(p);
+    }
+    *out = &d;
+    return CATS_OK;
+}
+}  // namespace
+
+int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const int32_t* parent, int32_t n_nodes,
+                                int32_t n_heads, int32_t head_dim, int32_t max_ctx, int32_t ctx_len, void* out,
+                                void* stream) {
+    if (!q || !out || !parent || !kv_ok(kv, 0, 1)) return CATS_EINVAL;
+    if (n_nodes < 1 || n_heads < 1 || (head_dim != 64 && head_dim != 128) || max_ctx < 64 || max_ctx % 64 != 0 ||
+        ctx_len < 0)
+        return CATS_EINVAL;
+    if (n_nodes > CATS_MAX_TREE) return CATS_ECAPACITY;
+    if (static_cast<int64_t>(ctx_len) + n_nodes > max_ctx) return CATS_ECAPACITY;
+    TreeUploadArgs up;
+    std::memset(&up, 0, sizeof up);
+    if (parent[0] != -1) return CATS_EINVAL;
+    up.parent[0] = -1;
+    for (int i = 1; i < n_nodes; ++i) {
+        const int p = parent[i];
+        if (p < 0 || p >= i) return CATS_EINVAL;
+        up.parent[i] = p;
+        up.depth[i] = up.depth[p] + 1;
+        if (up.depth[i] > CATS_MAX_DEPTH) return CATS_EINVAL;
+    }
+    NoallocDevice* dev = nullptr;
+    const int rc = noalloc_device(&dev);
+    if (rc != CATS_OK) return rc;
+
+    AttnArgs a;
+    a.q = static_cast<const bf16_t*>(q);
+    a.q_lo = nullptr;
+    a.out = static_cast<bf16_t*>(out);
+    a.out_lo = nullptr;
+    a.kc = static_cast<const bf16_t*>(kv->k);
+    a.vt = static_cast<const bf16_t*>(kv->v);
+    a.T = a.Tq = n_nodes;
+    a.q0 = 0;
+    a.H = n_heads * head_dim;
+    a.nh = n_heads;
+    a.d = head_dim;
+    a.max_ctx = max_ctx;
+    a.ctx_len = ctx_len;
+    const int n_keys = ctx_len + n_nodes;
+    const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
+    a.blocks_per_chunk = attn_blocks_per_chunk(n_nodes, n_heads, 32, dev->n_cus, n_keys);
+    a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
+    a.t_pad = (n_nodes + 31) / 32 * 32;
+    // layout of the scratch array: tree arrays, ancestor masks, then the chunk partials
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += align256(bytes);
+        return o;
+    };
+    const size_t o_tok = take(CATS_MAX_TREE * 4), o_par = take(CATS_MAX_TREE * 4), o_dep = take(CATS_MAX_TREE * 4);
+    const size_t o_anc = take(CATS_MAX_TREE * sizeof(u32x4));
+    const size_t slots = static_cast<size_t>(n_heads) * a.n_chunks * a.t_pad;
+    const size_t o_pml = take(slots * 2 * sizeof(float));
+    const size_t o_po = take(slots * head_dim * sizeof(float));
+    if (off > CATS_NOALLOC_SCRATCH_BYTES) return CATS_ECAPACITY;
+    unsigned char* b = dev->ptr;
+    int32_t* d_parent = reinterpret_cast<int32_t*>(b + o_par);
+    a.anc = reinterpret_cast<u32x4*>(b + o_anc);
+    a.pml = reinterpret_cast<float*>(b + o_pml);
+    a.po = reinterpret_cast<float*>(b + o_po);
+    hipStream_t st = as_stream(stream);
+    launch_tree_upload(up, n_nodes, reinterpret_cast<int32_t*>(b + o_tok), d_parent,
+                       reinterpret_cast<int32_t*>(b + o_dep), st);
+    launch_tree_masks(d_parent, n_nodes, reinterpret_cast<u32x4*>(b + o_anc), st);
+    launch_attention(a, st);
+    HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
 const char* cats_gemm_kernel_name(void) { return "cats_gemm_skinny_bf16"; }
 
 const char* cats_strerror(int status) {
     switch (status) {
         case CATS_OK: return "ok";
         case CATS_EINVAL: return "invalid argument (null pointer, bad shape, malformed tree or token out of range)";
-        case CATS_ECAPACITY: return "capacity exceeded (ctx_len + tree size > max_ctx, or more nodes than the arrays hold)";
+        case CATS_ECAPACITY:
+            return "capacity exceeded (ctx_len + tree size > max_ctx, more nodes than the arrays hold, or a shape too "
+                   "large for the fixed scratch of the no-allocation entry point)";
         case CATS_ESTATE: return "no tree has been set on this context";
         case CATS_EHIP: return hipGetErrorString(g_last_hip);
         default: return "unknown status";
