@@ -9,7 +9,7 @@ import pytest
 
 import paper_2605_11186_amd as cats
 import synth
-from test_oracle_pins import MICRO, algorithm1_walk, make_model
+from test_oracle_pins import MICRO, cascade_commit, make_model
 
 
 def token_paths(token, parent):
@@ -90,7 +90,7 @@ def test_accept_walk_on_built_trees_is_algorithm_1():
             return int(amax[node])
 
         acc = micro.accept(token, parent, depth, amax, 0)
-        assert acc["tokens"][1:] + [acc["bonus_token"]] == algorithm1_walk([int(t) for t in d], c_hat, argmax_at)
+        assert acc["tokens"][1:] + [acc["bonus_token"]] == cascade_commit([int(t) for t in d], c_hat, argmax_at)
 
 
 def test_error_codes():

@@ -211,12 +211,12 @@ def test_chain_tree_equals_causal_decoding(micro):
 def test_every_node_equals_its_own_path_all_small_trees(micro):
     ctx = synth.context_tokens(MICRO, 8, 3)
     n_trees = 0
-    for T in range(1, 6):
+    for T in range(1, 7):
         for parent, depth in synth.all_parent_arrays(T):
             tok = synth.distinct_sibling_tokens(parent, MICRO.vocab, 100 + n_trees)
             check_nodes_equal_own_paths(micro, ctx, parent, depth, tok)
             n_trees += 1
-    assert n_trees == 1 + 1 + 2 + 6 + 24
+    assert n_trees == 1 + 1 + 2 + 6 + 24 + 120
 
 
 def test_every_node_equals_its_own_path_binary_tree_and_empty_context(micro):
@@ -297,25 +297,26 @@ def test_accept_brute_force_small_trees(micro):
     assert n > 500
 
 
-def algorithm1_walk(d, c_hat, argmax_at):
-    """The walk of Algorithm 1 for a chain of drafts d[0..g-1] with shallow-verifier
-    corrections c_hat (dict position -> token).  argmax_at(prefix) is the target's greedy
-    token after root + prefix.  Reading used: the correction at position i is judged by the
-    same distribution as draft i (it is its sibling), and the bonus token is the target's
-    own prediction after the last accepted token."""
-    y = []
-    for i in range(len(d)):
-        if d[i] == argmax_at(tuple(y)):
-            y.append(d[i])
-        elif i in c_hat and c_hat[i] == argmax_at(tuple(y)):
-            y.append(c_hat[i])
-            break
-        else:
-            break
+def cascade_commit(d, c_hat, argmax_at):
+    """What one cascaded cycle commits (Algorithm 1, walk + bonus token) for a chain of drafts
+    d[0..g-1] with shallow-verifier corrections c_hat (dict position -> token), stated as a
+    property instead of a walk.  argmax_at(prefix) is the target's greedy token after
+    root + prefix.  Let m be the length of the longest draft prefix in which every draft equals
+    the target's greedy token after the drafts before it.  The committed tokens are that prefix,
+    then the correction at position m if there is one and it equals the target's greedy token
+    after the prefix (readings: the correction is judged by the distribution that judged the
+    draft it replaces; nothing follows an accepted correction, it is a leaf), then the target's
+    own greedy token after all of these (the bonus token)."""
+    g = len(d)
+    agrees = [d[j] == argmax_at(tuple(d[:j])) for j in range(g)]
+    m = agrees.index(False) if False in agrees else g
+    y = list(d[:m])
+    if m < g and c_hat.get(m) == argmax_at(tuple(y)):
+        y.append(c_hat[m])
     return y + [argmax_at(tuple(y))]
 
 
-def test_general_walk_equals_algorithm1_on_chain_plus_corrections(micro):
+def test_general_walk_commits_what_algorithm1_commits_on_chain_plus_corrections(micro):
     rng = np.random.default_rng(6)
     for trial in range(300):
         g = int(rng.integers(1, 7))
@@ -339,7 +340,7 @@ def test_general_walk_equals_algorithm1_on_chain_plus_corrections(micro):
             return int(amax[node])
 
         acc = micro.accept(token, parent, depth, amax, 0)
-        assert acc["tokens"][1:] + [acc["bonus_token"]] == algorithm1_walk(list(d), c_hat, argmax_at)
+        assert acc["tokens"][1:] + [acc["bonus_token"]] == cascade_commit(list(d), c_hat, argmax_at)
 
 
 def test_duplicate_siblings_pick_lowest_index(micro):
