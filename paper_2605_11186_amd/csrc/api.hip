@@ -39,6 +39,8 @@ struct cats_ctx {
     float2* rope_cs;  // [max_tree][d/2]
     float* attn_po;
     float* attn_pml;
+    int* attn_arrivals;        // [n_heads][4] chunk arrival counters (zero between launches)
+    bf16_t *k_lo, *vt_lo;      // low parts of the K/V rows that the running call appends (see AttnArgs)
     int attn_max_chunks;
     int32_t* amax;   // [max_tree]
     float *am_best, *am_second;   // [max_tree][ARGMAX_SLICES] slice results of the argmax
@@ -160,12 +162,18 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     return g.plan;
 }
 
+// with_lo: the call's own rows (nodes n0 .. n0 + rows - 1) have their low parts in the window
 void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const cats_kv_layer* kv,
-                       int ctx_len, bf16_t* out, bf16_t* out_lo, hipStream_t st) {
+                       int ctx_len, bf16_t* out, bf16_t* out_lo, bool with_lo, hipStream_t st) {
     AttnArgs a;
     a.q = q;
     a.q_lo = q_lo;
     a.out_lo = out_lo;
+    a.k_lo = with_lo ? c->k_lo : nullptr;
+    a.vt_lo = with_lo ? c->vt_lo : nullptr;
+    a.lo_begin = ctx_len + c->n0;
+    a.lo_end = with_lo ? ctx_len + c->n0 + c->rows : a.lo_begin;
+    a.arrivals = c->attn_arrivals;
     a.kc = static_cast<const bf16_t*>(kv->k);
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.anc = c->anc;
@@ -210,8 +218,11 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.d = c->d.head_dim;
     qa.max_ctx = c->d.max_ctx;
     qa.row0 = ctx_len + c->n0;
+    qa.k_lo = c->k_lo;
+    qa.vt_lo = c->vt_lo;
+    qa.win0 = ctx_len % ATTN_KB + c->n0;
     launch_qkv_rope(qa, st);
-    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, st);
+    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
     plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
@@ -402,6 +413,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
     const size_t o_pml = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * 2 * 4);
+    const size_t o_aarr = take(static_cast<size_t>(d.n_heads) * 4 * 4);   // zero from the memset below
+    const size_t o_klo = take(static_cast<size_t>(d.n_heads) * TREE_WIN * d.head_dim * 2);
+    const size_t o_vlo = take(static_cast<size_t>(d.n_heads) * TREE_WIN * d.head_dim * 2);
     const size_t o_amax = take(Tm * 4);
     const size_t o_sb = take(Tm * ARGMAX_SLICES * 4), o_s2 = take(Tm * ARGMAX_SLICES * 4);
     const size_t o_si = take(Tm * ARGMAX_SLICES * 4), o_arr = take(Tm * 4);   // zero from the memset below
@@ -440,6 +454,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->rope_cs = reinterpret_cast<float2*>(b + o_cs);
     c->attn_po = reinterpret_cast<float*>(b + o_po);
     c->attn_pml = reinterpret_cast<float*>(b + o_pml);
+    c->attn_arrivals = reinterpret_cast<int*>(b + o_aarr);
+    c->k_lo = reinterpret_cast<bf16_t*>(b + o_klo);
+    c->vt_lo = reinterpret_cast<bf16_t*>(b + o_vlo);
     c->amax = reinterpret_cast<int32_t*>(b + o_amax);
     c->am_best = reinterpret_cast<float*>(b + o_sb);
     c->am_second = reinterpret_cast<float*>(b + o_s2);
@@ -529,7 +546,7 @@ int cats_tree_attention(cats_ctx* ctx, const void* q, const cats_kv_layer* kv, i
     if (rc != CATS_OK) return rc;
     if (!q || !out || !kv_ok(kv, 0, 1)) return CATS_EINVAL;
     enqueue_attention(ctx, static_cast<const bf16_t*>(q), nullptr, kv, ctx_len, static_cast<bf16_t*>(out),
-                      nullptr, as_stream(stream));
+                      nullptr, false, as_stream(stream));
     HIP_TRY(hipGetLastError());
     return CATS_OK;
 }
@@ -948,6 +965,8 @@ int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const in
     a.q_lo = nullptr;
     a.out = static_cast<bf16_t*>(out);
     a.out_lo = nullptr;
+    a.k_lo = a.vt_lo = nullptr;
+    a.lo_begin = a.lo_end = ctx_len;
     a.kc = static_cast<const bf16_t*>(kv->k);
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.T = a.Tq = n_nodes;
@@ -971,6 +990,8 @@ int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const in
     };
     const size_t o_tok = take(CATS_MAX_TREE * 4), o_par = take(CATS_MAX_TREE * 4), o_dep = take(CATS_MAX_TREE * 4);
     const size_t o_anc = take(CATS_MAX_TREE * sizeof(u32x4));
+    const int n_counters = n_heads * (a.t_pad / 32);
+    const size_t o_arr = take(static_cast<size_t>(n_counters) * sizeof(int));
     const size_t slots = static_cast<size_t>(n_heads) * a.n_chunks * a.t_pad;
     const size_t o_pml = take(slots * 2 * sizeof(float));
     const size_t o_po = take(slots * head_dim * sizeof(float));
@@ -980,7 +1001,10 @@ int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const in
     a.anc = reinterpret_cast<u32x4*>(b + o_anc);
     a.pml = reinterpret_cast<float*>(b + o_pml);
     a.po = reinterpret_cast<float*>(b + o_po);
+    a.arrivals = reinterpret_cast<int*>(b + o_arr);
     hipStream_t st = as_stream(stream);
+    // the array keeps whatever the last call left: the arrival counters must start at zero
+    launch_zero_i32(a.arrivals, n_counters, st);
     launch_tree_upload(up, n_nodes, reinterpret_cast<int32_t*>(b + o_tok), d_parent,
                        reinterpret_cast<int32_t*>(b + o_dep), st);
     launch_tree_masks(d_parent, n_nodes, reinterpret_cast<u32x4*>(b + o_anc), st);

@@ -167,8 +167,11 @@ struct QkvRopeArgs {
     bf16_t* q_lo;       // [T][H] low parts
     bf16_t* kc;         // [nh][max_ctx][d]
     bf16_t* vt;         // [nh][d][max_ctx]
+    bf16_t* k_lo;       // [nh][TREE_WIN][d]   low parts of the key rows written here (see AttnArgs)
+    bf16_t* vt_lo;      // [nh][d][TREE_WIN]   low parts of the value columns
     int T, H, nh, d, max_ctx;
     int row0;           // cache row of the first of the T rows (ctx_len + index of its node)
+    int win0;           // window index of that row: row0 - (ctx_len rounded down to a multiple of 32)
 };
 void launch_qkv_rope(const QkvRopeArgs& a, hipStream_t st);
 
@@ -209,17 +212,28 @@ constexpr int ARGMAX_SLICES = 16;
 void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
 
 // ---------------------------------------------------------------- attention
+// The cache holds bf16 rows.  The rows that the running call itself appends (the tree nodes it
+// forwards) also keep their rounding remainders (k - bf16(k), as bf16) in a small window beside
+// the cache, so that within the call tree nodes see one another's keys and values to about 16
+// mantissa bits; once committed, a row is its bf16 cache entry.  Window index of cache row r:
+// r - (ctx_len & ~31), i.e. the window starts at the 32-key block that holds row ctx_len, which
+// keeps 8-key vector loads 16-byte aligned.  Entries outside [lo_begin, lo_end) are stale.
+constexpr int TREE_WIN = 32 + CATS_MAX_TREE;   // rows of the window
 struct AttnArgs {
     const bf16_t* q;        // [Tq][H]
     const bf16_t* q_lo;     // optional [Tq][H] low parts of q
     const bf16_t* kc;       // [nh][max_ctx][d]
     const bf16_t* vt;       // [nh][d][max_ctx]
+    const bf16_t* k_lo;     // optional [nh][TREE_WIN][d] low parts of key rows lo_begin .. lo_end - 1
+    const bf16_t* vt_lo;    // optional [nh][d][TREE_WIN]
+    int lo_begin, lo_end;   // cache rows that have low parts (empty range: none)
     const u32x4* anc;       // device [T] ancestor-or-self masks (cats_tree_masks)
     int T, H, nh, d, max_ctx, ctx_len;   // T: tree nodes whose K/V rows ctx_len.. take part as keys
     int Tq, q0;             // the queries are nodes q0 .. q0+Tq-1 (rows 0..Tq-1 of q / out)
     int blocks_per_chunk, n_chunks, t_pad;
     float* po;              // [nh][n_chunks][t_pad][d]
     float* pml;             // [nh][n_chunks][t_pad][2]
+    int* arrivals;          // [nh][t_pad / 32] chunk arrival counters, zero between launches
     bf16_t* out;            // [Tq][H]
     bf16_t* out_lo;         // optional [Tq][H] low parts of the output
 };
@@ -227,6 +241,7 @@ constexpr int ATTN_KB = 32;    // keys per block
 constexpr int ATTN_WAVES = 4;  // waves per attention workgroup, each taking every 4th block
 void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st);
 void launch_attention(const AttnArgs& a, hipStream_t st);
+void launch_zero_i32(int* p, int n, hipStream_t st);   // fill kernel (a memset node must not enter a captured graph)
 
 // ---------------------------------------------------------------- accept / compact
 struct TreeUploadArgs {

@@ -66,13 +66,14 @@ __global__ void cats_rope_table(RopeTableArgs a) {
 
 // Adds up q|k|v partials, scales by the row's norm factor, rotates q and k (pairs j, j+d/2),
 // writes q (high and low bf16 parts) and appends the key row and the (transposed) value column
-// of row t at cache row row0 + t.  All piece loads are 16-byte loads issued in batches.
+// of row t at cache row row0 + t (bf16), with their rounding remainders in the low-part window
+// (see AttnArgs).  All piece loads are 16-byte loads issued in batches.
 // Blocks [0, T * gy): q and k, one thread per (node, head, 4 consecutive pairs).
 // Blocks after those: values, one block per (head, 32 dims): the sums go through LDS so that
 // the stores into the transposed cache run along the node index (contiguous in memory).
 constexpr int V_DIMS = 32;   // head dims per value block
 __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
-    __shared__ bf16_t s_v[V_DIMS][CATS_MAX_TREE + 2];
+    __shared__ bf16_t s_v[2][V_DIMS][CATS_MAX_TREE + 2];   // [0] high parts, [1] low parts
     const int half = a.d / 2;
     const int N = 3 * a.H;
     const size_t stride = static_cast<size_t>(a.T) * N;
@@ -94,15 +95,26 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
             vb4 *= row_scale(a.ns, cb);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (ta < a.T) s_v[4 * (threadIdx.x & 7) + e][ta] = f2bf(va[e]);
-                if (tb < a.T) s_v[4 * (threadIdx.x & 7) + e][tb] = f2bf(vb4[e]);
+                const bf16_t ha = f2bf(va[e]), hb = f2bf(vb4[e]);
+                if (ta < a.T) {
+                    s_v[0][4 * (threadIdx.x & 7) + e][ta] = ha;
+                    s_v[1][4 * (threadIdx.x & 7) + e][ta] = f2bf(va[e] - bf2f(ha));
+                }
+                if (tb < a.T) {
+                    s_v[0][4 * (threadIdx.x & 7) + e][tb] = hb;
+                    s_v[1][4 * (threadIdx.x & 7) + e][tb] = f2bf(vb4[e] - bf2f(hb));
+                }
             }
         }
         __syncthreads();
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
         bf16_t* vt = a.vt + (static_cast<size_t>(h) * a.d + ds) * a.max_ctx + a.row0;
+        bf16_t* vl = a.vt_lo + (static_cast<size_t>(h) * a.d + ds) * TREE_WIN + a.win0;
         for (int dd = wave; dd < V_DIMS; dd += 4)
-            for (int t = lane; t < a.T; t += 64) vt[static_cast<size_t>(dd) * a.max_ctx + t] = s_v[dd][t];
+            for (int t = lane; t < a.T; t += 64) {
+                vt[static_cast<size_t>(dd) * a.max_ctx + t] = s_v[0][dd][t];
+                vl[dd * TREE_WIN + t] = s_v[1][dd][t];
+            }
         return;
     }
     const int t = blockIdx.x / gy, h = (blockIdx.x - t * gy) * heads_per_block + threadIdx.x / threads_per_head;
@@ -125,6 +137,7 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
     for (int m = 0; m < 4; ++m) v4[m] *= rs;
     const size_t qo = static_cast<size_t>(t) * a.H + c0;
     bf16_t* k = a.kc + (static_cast<size_t>(h) * a.max_ctx + a.row0 + t) * a.d + j;
+    bf16_t* kl = a.k_lo + (static_cast<size_t>(h) * TREE_WIN + a.win0 + t) * a.d + j;
     float q0[4], q1[4], k0[4], k1[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -134,17 +147,23 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         k0[e] = v4[2][e] * cs.x - v4[3][e] * cs.y;
         k1[e] = v4[2][e] * cs.y + v4[3][e] * cs.x;
     }
-    uint2 qh0, ql0, qh1, ql1;
+    uint2 qh0, ql0, qh1, ql1, kh0, kl0, kh1, kl1;
     split_bf2(q0[0], q0[1], qh0.x, ql0.x);
     split_bf2(q0[2], q0[3], qh0.y, ql0.y);
     split_bf2(q1[0], q1[1], qh1.x, ql1.x);
     split_bf2(q1[2], q1[3], qh1.y, ql1.y);
+    split_bf2(k0[0], k0[1], kh0.x, kl0.x);
+    split_bf2(k0[2], k0[3], kh0.y, kl0.y);
+    split_bf2(k1[0], k1[1], kh1.x, kl1.x);
+    split_bf2(k1[2], k1[3], kh1.y, kl1.y);
     *reinterpret_cast<uint2*>(a.q + qo) = qh0;
     *reinterpret_cast<uint2*>(a.q_lo + qo) = ql0;
     *reinterpret_cast<uint2*>(a.q + qo + half) = qh1;
     *reinterpret_cast<uint2*>(a.q_lo + qo + half) = ql1;
-    *reinterpret_cast<uint2*>(k) = make_uint2(pack_bf2(k0[0], k0[1]), pack_bf2(k0[2], k0[3]));
-    *reinterpret_cast<uint2*>(k + half) = make_uint2(pack_bf2(k1[0], k1[1]), pack_bf2(k1[2], k1[3]));
+    *reinterpret_cast<uint2*>(k) = kh0;
+    *reinterpret_cast<uint2*>(k + half) = kh1;
+    *reinterpret_cast<uint2*>(kl) = kl0;
+    *reinterpret_cast<uint2*>(kl + half) = kl1;
 }
 
 // h[t][n] = silu(gate[t][n]) * up[t][n] after scaling both by the row's norm factor; four

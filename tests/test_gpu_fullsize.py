@@ -109,7 +109,6 @@ def test_7b_full_verify_step_matches_oracle():
         pair.close()
 
 
-@pytest.mark.skip(reason="waits for the tree's own K/V rows at full precision inside a step: with bf16 tree rows the third iteration measures 2.06e-2")
 @pytest.mark.timeout(1000)
 def test_13b_full_depth_iterations_match_oracle():
     """Config 4 at full depth: the 13B-shaped 40-layer model, KV context 2048, 64-node trees of
@@ -118,7 +117,10 @@ def test_13b_full_depth_iterations_match_oracle():
     (the first child at each level carries the true next token with probability 0.8, as in the
     benchmark's iteration workload) and from seeded random numbers, never from the GPU.  Compared
     per iteration: hidden states and logits of all 64 nodes, argmax where the oracle's margin
-    allows, the accept result, and the compacted cache rows."""
+    allows, the accept result, and the compacted cache rows.  The KV cache is a bf16 array at the
+    library's boundary: a step reads bf16 rows and commits bf16 rows, so between two steps the
+    rows that the oracle has just committed are rounded to bf16 here (a format conversion of the
+    next step's input; inside a step both sides keep the tree's own rows at full precision)."""
     dims = synth.V13B
     S0, T, n_iter, n_ref = 2048, 64, 3, 10
     pair = Pair(dims, 13, max_ctx=S0 + 192, max_tree=T, precision="f32", packed=True)
@@ -174,6 +176,8 @@ def test_13b_full_depth_iterations_match_oracle():
                 gk, gv = pair.device_rows(ks, vs, l, new_S)
                 assert rel_err(gk[S:], kc[l, S:new_S]) <= REL_TOL
                 assert rel_err(gv[S:], vc[l, S:new_S]) <= REL_TOL
+            for c in (kc, vc):
+                c[:, S:new_S] = synth.f32_from_bf16_bits(synth.bf16_bits_from_f32(np.ascontiguousarray(c[:, S:new_S])))
             committed += o_acc["tokens"][1:] + [o_acc["bonus_token"]]
             S, root = new_S, o_acc["bonus_token"]
         # speculative greedy is lossless: what was committed is the oracle's plain greedy stream
