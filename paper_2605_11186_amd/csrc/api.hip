@@ -39,7 +39,7 @@ struct cats_ctx {
     float2* rope_cs;  // [max_tree][d/2]
     float* attn_po;
     float* attn_pml;
-    int* attn_arrivals;        // [n_heads][4] chunk arrival counters (zero between launches)
+    int* attn_arrivals;        // [n_heads][query groups] chunk arrival counters (zero between launches)
     bf16_t *k_lo, *vt_lo;      // low parts of the K/V rows that the running call appends (see AttnArgs)
     int attn_max_chunks;
     int32_t* amax;   // [max_tree]
@@ -92,15 +92,14 @@ int target_wgs(const cats_ctx* c) { return c->n_cus; }
 int gemm_kc(int rows) { return rows <= 32 ? 2 * GEMM_KC : GEMM_KC; }
 int gemm_bn(int rows) { return rows <= 32 ? 128 : 256; }
 
-// Key blocks per attention chunk: aim at one wave per SIMD (four SIMDs per compute unit; the
-// kernel needs most of the register file): heads * chunks * query groups * waves per workgroup.
-int attn_blocks_per_chunk(int rows, int n_heads, int max_chunks, int n_cus, int n_keys) {
+// Key chunks per (head, query group): the launch has heads * query groups * chunks workgroups,
+// about one per compute unit (the kernel's register footprint allows one four-wave workgroup
+// per unit); more chunks than that only add hand-over traffic between workgroups.
+int attn_chunks(int rows, int n_heads, int max_chunks, int n_cus, int n_keys) {
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    const int tq = (rows + 31) / 32;
-    const int wave_target = 4 * n_cus;
-    int chunks = std::max(1, wave_target / std::max(1, n_heads * tq * ATTN_WAVES));
-    chunks = std::min(chunks, std::min(n_blocks, max_chunks));
-    return (n_blocks + chunks - 1) / chunks;
+    const int groups = (rows + ATTN_QN - 1) / ATTN_QN;
+    const int chunks = std::max(1, n_cus / std::max(1, n_heads * groups));
+    return std::min(chunks, std::min(n_blocks, max_chunks));
 }
 
 hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
@@ -186,9 +185,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.max_ctx = c->d.max_ctx;
     a.ctx_len = ctx_len;
     const int n_keys = ctx_len + c->T;
-    a.blocks_per_chunk = attn_blocks_per_chunk(c->rows, c->d.n_heads, c->attn_max_chunks, c->n_cus, n_keys);
-    const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
+    a.n_chunks = attn_chunks(c->rows, c->d.n_heads, c->attn_max_chunks, c->n_cus, n_keys);
     a.t_pad = (a.Tq + 31) / 32 * 32;
     a.po = c->attn_po;
     a.pml = c->attn_pml;
@@ -413,7 +410,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
     const size_t o_pml = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * 2 * 4);
-    const size_t o_aarr = take(static_cast<size_t>(d.n_heads) * 4 * 4);   // zero from the memset below
+    const size_t o_aarr = take(static_cast<size_t>(d.n_heads) * ATTN_MAX_QGROUPS * 4);   // zero from the memset below
     const size_t o_klo = take(static_cast<size_t>(d.n_heads) * TREE_WIN * d.head_dim * 2);
     const size_t o_vlo = take(static_cast<size_t>(d.n_heads) * TREE_WIN * d.head_dim * 2);
     const size_t o_amax = take(Tm * 4);
@@ -978,8 +975,7 @@ int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const in
     a.ctx_len = ctx_len;
     const int n_keys = ctx_len + n_nodes;
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    a.blocks_per_chunk = attn_blocks_per_chunk(n_nodes, n_heads, 32, dev->n_cus, n_keys);
-    a.n_chunks = (n_blocks + a.blocks_per_chunk - 1) / a.blocks_per_chunk;
+    a.n_chunks = attn_chunks(n_nodes, n_heads, 32, dev->n_cus, n_keys);
     a.t_pad = (n_nodes + 31) / 32 * 32;
     // layout of the scratch array: tree arrays, ancestor masks, then the chunk partials
     size_t off = 0;
@@ -990,7 +986,7 @@ int cats_tree_attention_noalloc(const void* q, const cats_kv_layer* kv, const in
     };
     const size_t o_tok = take(CATS_MAX_TREE * 4), o_par = take(CATS_MAX_TREE * 4), o_dep = take(CATS_MAX_TREE * 4);
     const size_t o_anc = take(CATS_MAX_TREE * sizeof(u32x4));
-    const int n_counters = n_heads * (a.t_pad / 32);
+    const int n_counters = n_heads * ((n_nodes + ATTN_QN - 1) / ATTN_QN);
     const size_t o_arr = take(static_cast<size_t>(n_counters) * sizeof(int));
     const size_t slots = static_cast<size_t>(n_heads) * a.n_chunks * a.t_pad;
     const size_t o_pml = take(slots * 2 * sizeof(float));

@@ -6,7 +6,7 @@
 // LDS by cats_tree_masks when the tree is uploaded and read here one mask per query.
 //
 // Work split: one workgroup of ATTN_WAVES waves per (head, chunk of key blocks, group of
-// 32 queries); wave w takes the chunk's blocks w, w + ATTN_WAVES, ... and the waves'
+// ATTN_QN queries); wave w takes the chunk's blocks w, w + ATTN_WAVES, ... and the waves'
 // partial results are merged through LDS.  With more than one chunk the workgroup then
 // publishes its chunk's result, and the last workgroup of a (head, query group) to arrive adds
 // up all chunks in chunk order with the usual log-sum-exp rescaling and writes the output:
@@ -54,33 +54,35 @@ __device__ __forceinline__ void wait_coherent(f32x4& v) { asm volatile("s_waitcn
 // MFMA 16x16x32 bf16 (wave64): lane l supplies, for A, row l%16 and
 // k = 8*(l/16)..+7; for B, column l%16 and the same k; its 4 results are
 // D[4*(l/16) + r][l%16].
-template <int D>
-__global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(AttnArgs a) {
+// QB: 16-query groups per wave (a workgroup covers QN = 16 * QB queries); W: waves per workgroup.
+template <int D, int QB, int W>
+__global__ __launch_bounds__(64 * W) void cats_tree_attention_kernel(AttnArgs a) {
+    constexpr int QN = 16 * QB;
     constexpr int KS = D / 32;  // k-steps of the score product
     constexpr int DB = D / 16;  // 16-row blocks of O^T
-    __shared__ float s_o[ATTN_WAVES][32][D + 4];
-    __shared__ float s_ml[ATTN_WAVES][32][2];
+    __shared__ float s_o[W][QN][D + 4];
+    __shared__ float s_ml[W][QN][2];
     __shared__ int s_last;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, q4 = lane >> 4;
-    const int chunk = blockIdx.x, h = blockIdx.y, qbase = blockIdx.z * 32;
+    const int chunk = blockIdx.x, h = blockIdx.y, qbase = blockIdx.z * QN;
     const int S = a.ctx_len, T = a.T, Tq = a.Tq;   // T tree nodes are keys; Tq of them (from q0) are queries
     const int n_keys = S + T;
 
-    // ancestor-or-self masks of this lane's two queries
-    u32x4 anc[2];
+    // ancestor-or-self masks of this lane's queries
+    u32x4 anc[QB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int t = qbase + 16 * qb + m;
         anc[qb] = t < Tq ? a.anc[a.q0 + t] : u32x4{0u, 0u, 0u, 0u};
     }
 
     // Q^T fragments (B operand of the score product): column = query, k = dim; queries come
     // as high + low bf16 parts (the low part may be absent)
-    bf16x8 qf[2][KS], qfl[2][KS];
+    bf16x8 qf[QB][KS], qfl[QB][KS];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         const int t = qbase + 16 * qb + m;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
@@ -95,21 +97,38 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
         }
     }
 
-    f32x4 o[2][DB];
+    f32x4 o[QB][DB];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int db = 0; db < DB; ++db) o[qb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float mrun[2] = {-1e30f, -1e30f};
-    float lrun[2] = {0.f, 0.f};  // this lane's share of the row sum
+    float mrun[QB], lrun[QB];   // running maximum (base 2), this lane's share of the row sum
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        mrun[qb] = -1e30f;
+        lrun[qb] = 0.f;
+    }
+    bool fresh = true;           // nothing accumulated yet (wave-uniform)
 
-    const float scale = rsqrtf(static_cast<float>(D));
+    const float scale = rsqrtf(static_cast<float>(D)) * 1.44269504088896340736f;   // 1/sqrt(d) * log2(e)
     const bf16_t* kbase = a.kc + static_cast<size_t>(h) * a.max_ctx * D;
     const bf16_t* vbase = a.vt + static_cast<size_t>(h) * D * a.max_ctx;
 
     const int n_blocks = (n_keys + ATTN_KB - 1) / ATTN_KB;
-    const int blk_begin = chunk * a.blocks_per_chunk;
-    const int blk_end = min(n_blocks, blk_begin + a.blocks_per_chunk);
+    // Chunks are contiguous runs of key blocks (neighbouring blocks share cache lines of the
+    // transposed values) of equal cost: a block that holds tree rows counts twice (masks, low
+    // parts, no prefetch), so the chunk that ends with them gets fewer blocks.  Cost units: block b
+    // starts at unit b below the first tree block tb, at tb + 2 (b - tb) from there on; chunk c
+    // owns the blocks whose first unit lies in [c U / n, (c + 1) U / n).
+    const int tree_blk = min(n_blocks, S / ATTN_KB);
+    const int units = tree_blk + 2 * (n_blocks - tree_blk);
+    auto first_block_at = [&](int u) {   // first block whose first unit is >= u
+        return u <= tree_blk ? u : tree_blk + (u - tree_blk + 1) / 2;
+    };
+    const int blk_begin = first_block_at((chunk * units + a.n_chunks - 1) / a.n_chunks);
+    const int blk_end = chunk + 1 == a.n_chunks ? n_blocks
+                                                : first_block_at(((chunk + 1) * units + a.n_chunks - 1) / a.n_chunks);
+    constexpr int blk_stride = W;
 
     // The K / V fragments of one 32-key block.  Score-block rows are permuted so that a lane
     // ends up with 8 consecutive keys: sub-block b, MFMA row mm <-> key j0 + 8*(mm/4) + 4*b + mm%4.
@@ -159,22 +178,25 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // LO: the block also has low parts of keys (kfl) and values (vfl)
+    // MODE 0: every key of the block is a context row (no mask, no tail: straight-line code);
+    // MODE 1: the block may hold tree rows and rows past the tree; MODE 2: as 1, and the block
+    // also has low parts of keys (kfl) and values (vfl).  Scores and running maxima are kept in
+    // the base-2 domain (the scale carries log2 e), so that every exponential is one v_exp_f32.
     auto compute_block = [&](const bf16x8 (&kf)[2][KS], const bf16x8 (&vf_in)[DB], const bf16x8 (&kfl)[2][KS],
-                             const bf16x8 (&vfl)[DB], int blk, auto lo_tag) {
-        constexpr bool LO = decltype(lo_tag)::value;
+                             const bf16x8 (&vfl)[DB], int blk, auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        constexpr bool LO = MODE == 2;
         const int j0 = blk * ATTN_KB;
         const int key0 = j0 + 8 * q4;
         bf16x8 vf[DB];
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
             u32x4 v = __builtin_bit_cast(u32x4, vf_in[db]);
-            if (key0 + 8 > n_keys) v = keep_keys(v, key0, 0, n_keys);  // rows past the tree may hold anything
+            if constexpr (MODE != 0) v = keep_keys(v, key0, 0, n_keys);  // rows past the tree may hold anything
             vf[db] = as_bf16x8(v);
         }
-        const bool all_ctx = j0 + ATTN_KB <= S;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
             f32x4 st[2];
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
@@ -193,17 +215,17 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
             float bmax = -1e30f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int key = key0 + i;
                 bool v = true;
-                if (!all_ctx) {
-                    const int rel = key - S;
-                    v = rel < 0;
-                    if (rel >= 0 && rel < T) {
-                        const int w = rel >> 5;
-                        const u32x4 am = anc[qb];
-                        const uint32_t word = w == 0 ? am[0] : (w == 1 ? am[1] : (w == 2 ? am[2] : am[3]));
-                        v = (word >> (rel & 31)) & 1u;
-                    }
+                if constexpr (MODE != 0) {
+                    // branch-free: the ancestor word is picked with selects, a key outside the
+                    // tree's rows reads bit 0 of a zero word
+                    const int rel = key0 + i - S;
+                    const bool in_tree = rel >= 0 && rel < T;
+                    const int w = rel >> 5;
+                    const u32x4 am = anc[qb];
+                    uint32_t word = w == 0 ? am[0] : (w == 1 ? am[1] : (w == 2 ? am[2] : am[3]));
+                    word = in_tree ? word : 0u;
+                    v = rel < 0 || ((word >> (rel & 31)) & 1u);
                 }
                 vis[i] = v;
                 sc[i] = v ? st[i >> 2][i & 3] * scale : -1e30f;
@@ -211,17 +233,30 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
             }
             bmax = fmaxf(bmax, __shfl_xor(bmax, 16));
             bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
-            const float mnew = fmaxf(mrun[qb], bmax);
-            const float alpha = __expf(mrun[qb] - mnew);
-            mrun[qb] = mnew;
+            // The running maximum may lag behind the true one by up to 8 (base 2): the
+            // probabilities then reach 2^8 at most, and the accumulated output is rescaled only
+            // when some lane of the wave needs it (wave-uniform branch; rare after the first
+            // block), which saves the pass over the accumulators in the common case.
+            if (__builtin_amdgcn_ballot_w64(bmax > mrun[qb] + 8.f) != 0) {
+                const float mnew = fmaxf(mrun[qb], bmax);
+                const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
+                mrun[qb] = mnew;
+                lrun[qb] *= alpha;
+                if (!fresh) {
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) o[qb][db] *= alpha;
+                }
+            }
+            const float mref = mrun[qb];
             float p[8];
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                p[i] = vis[i] ? __expf(sc[i] - mnew) : 0.f;
+                const float e = __builtin_amdgcn_exp2f(sc[i] - mref);
+                p[i] = (MODE == 0 || vis[i]) ? e : 0.f;
                 psum += p[i];
             }
-            lrun[qb] = lrun[qb] * alpha + psum;
+            lrun[qb] += psum;
             // probabilities as high + low bf16 parts: the second product sees them to ~16 bits
             u32x4 pv, pvl;
 #pragma unroll
@@ -234,49 +269,58 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
             const bf16x8 pf = as_bf16x8(pv), pfl = as_bf16x8(pvl);
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                o[qb][db] *= alpha;
                 o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pf, o[qb][db], 0, 0, 0);
                 o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[db], pfl, o[qb][db], 0, 0, 0);
                 if constexpr (LO)
                     o[qb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vfl[db], pf, o[qb][db], 0, 0, 0);
             }
         }
+        fresh = false;
     };
 
-    // Two register sets.  Blocks without low parts: the fragments of block b+1 are requested
-    // before block b is multiplied, so the cache latency of one block hides behind the
-    // arithmetic of the other.  Blocks with low parts (the last ones, at most five per head):
-    // set A holds the high parts, set B the low parts.
+    // Two register sets.  This wave's blocks come in three runs.  Context-only blocks (all of
+    // them but the last few): the fragments of block b+1 are requested before block b is
+    // multiplied, so the cache latency of one block hides behind the arithmetic of the other.
+    // Then the blocks that hold tree rows without low parts (rows an earlier call appended, or a
+    // caller's own rows), one at a time; then the blocks with low parts, set A holding the high
+    // parts and set B the low parts.  The last two runs are at most five blocks per head.
     bf16x8 kfA[2][KS], kfB[2][KS], vfA[DB], vfB[DB];
     const bool have_lo = a.k_lo != nullptr && a.lo_end > a.lo_begin;
-    const int plain_end = have_lo ? min(blk_end, a.lo_begin / ATTN_KB) : blk_end;
+    const int lo_blk = have_lo ? min(blk_end, a.lo_begin / ATTN_KB) : blk_end;   // first block with low parts
+    const int ctx_end = min(lo_blk, tree_blk);                                // blocks below hold context rows only
     const int my_begin = blk_begin + wave;
-    if (my_begin < plain_end) {
-        const int last = my_begin + (plain_end - 1 - my_begin) / ATTN_WAVES * ATTN_WAVES;  // this wave's last plain block
-        load_block(kfA, vfA, my_begin);
-        for (int blk = my_begin; blk < plain_end; blk += 2 * ATTN_WAVES) {
-            load_block(kfB, vfB, min(blk + ATTN_WAVES, last));
-            compute_block(kfA, vfA, kfB, vfB, blk, std::false_type{});
-            if (blk + ATTN_WAVES < plain_end) {
-                load_block(kfA, vfA, min(blk + 2 * ATTN_WAVES, last));
-                compute_block(kfB, vfB, kfA, vfA, blk + ATTN_WAVES, std::false_type{});
-            }
-        }
-    }
+    // this wave's first block at or after `from`
+    auto my_first = [&](int from) {
+        return my_begin + (max(from - my_begin, 0) + blk_stride - 1) / blk_stride * blk_stride;
+    };
+    // the costlier blocks first: their loads go out with the kernel's first requests
     if (have_lo) {
-        // this wave's first block at or after plain_end
-        const int skipped = max(plain_end - my_begin, 0);
-        for (int blk = my_begin + (skipped + ATTN_WAVES - 1) / ATTN_WAVES * ATTN_WAVES; blk < blk_end;
-             blk += ATTN_WAVES) {
+        for (int blk = my_first(lo_blk); blk < blk_end; blk += blk_stride) {
             load_block(kfA, vfA, blk);
             load_block_lo(kfB, vfB, blk);
-            compute_block(kfA, vfA, kfB, vfB, blk, std::true_type{});
+            compute_block(kfA, vfA, kfB, vfB, blk, std::integral_constant<int, 2>{});
+        }
+    }
+    for (int blk = my_first(ctx_end); blk < lo_blk; blk += blk_stride) {
+        load_block(kfA, vfA, blk);
+        compute_block(kfA, vfA, kfB, vfB, blk, std::integral_constant<int, 1>{});
+    }
+    if (my_begin < ctx_end) {
+        const int last = my_begin + (ctx_end - 1 - my_begin) / blk_stride * blk_stride;  // this wave's last such block
+        load_block(kfA, vfA, my_begin);
+        for (int blk = my_begin; blk < ctx_end; blk += 2 * blk_stride) {
+            load_block(kfB, vfB, min(blk + blk_stride, last));
+            compute_block(kfA, vfA, kfB, vfB, blk, std::integral_constant<int, 0>{});
+            if (blk + blk_stride < ctx_end) {
+                load_block(kfA, vfA, min(blk + 2 * blk_stride, last));
+                compute_block(kfB, vfB, kfA, vfA, blk + blk_stride, std::integral_constant<int, 0>{});
+            }
         }
     }
 
     // every wave parks its running max, row sum and unnormalised output in LDS ...
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         float l = lrun[qb];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
@@ -291,18 +335,19 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
     }
     __syncthreads();
     // ... and the workgroup merges them (fixed wave order) into the chunk's result.
-    // thread -> (query ql, dims 32 i + 4 c .. + 3 for i < D/32): the eight threads of a query
-    // cover 32 consecutive dims per i, so every 16-byte access of a wave falls into whole
-    // 128-byte lines
-    constexpr int NI = D / 32;
-    const int ql = threadIdx.x >> 3, c4 = 4 * (threadIdx.x & 7);
+    // thread -> (query ql, dims 4 (i TPQ + c) .. + 3 for i < NI): the TPQ threads of a query cover
+    // 4 TPQ consecutive dims per i, so every 16-byte access of a wave falls into whole 128-byte lines
+    constexpr int TPQ = 64 * W / QN;      // threads per query
+    constexpr int NI = D / (4 * TPQ);
+    static_assert(NI >= 1 && NI * 4 * TPQ == D, "merge mapping");
+    const int ql = threadIdx.x / TPQ, c4 = 4 * (threadIdx.x % TPQ);
     float M = -1e30f;
 #pragma unroll
-    for (int w = 0; w < ATTN_WAVES; ++w) M = fmaxf(M, s_ml[w][ql][0]);
-    float wgt[ATTN_WAVES], l = 0.f;
+    for (int w = 0; w < W; ++w) M = fmaxf(M, s_ml[w][ql][0]);
+    float wgt[W], l = 0.f;
 #pragma unroll
-    for (int w = 0; w < ATTN_WAVES; ++w) {
-        wgt[w] = __expf(s_ml[w][ql][0] - M);
+    for (int w = 0; w < W; ++w) {
+        wgt[w] = __builtin_amdgcn_exp2f(s_ml[w][ql][0] - M);
         l += wgt[w] * s_ml[w][ql][1];
     }
     f32x4 acc[NI];
@@ -310,7 +355,7 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
     for (int i = 0; i < NI; ++i) {
         acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < ATTN_WAVES; ++w) acc[i] += wgt[w] * *reinterpret_cast<const f32x4*>(&s_o[w][ql][32 * i + c4]);
+        for (int w = 0; w < W; ++w) acc[i] += wgt[w] * *reinterpret_cast<const f32x4*>(&s_o[w][ql][4 * TPQ * i + c4]);
     }
 
     // out[t][h*D + dims] = num / den as high (+ low) bf16 parts
@@ -324,8 +369,8 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
             uint2 hi, lo;
             split_bf2(num[i][0] * inv, num[i][1] * inv, hi.x, lo.x);
             split_bf2(num[i][2] * inv, num[i][3] * inv, hi.y, lo.y);
-            *reinterpret_cast<uint2*>(a.out + o_off + 32 * i) = hi;
-            if (a.out_lo) *reinterpret_cast<uint2*>(a.out_lo + o_off + 32 * i) = lo;
+            *reinterpret_cast<uint2*>(a.out + o_off + 4 * TPQ * i) = hi;
+            if (a.out_lo) *reinterpret_cast<uint2*>(a.out_lo + o_off + 4 * TPQ * i) = lo;
         }
     };
     if (a.n_chunks == 1) {
@@ -340,51 +385,57 @@ __global__ __launch_bounds__(64 * ATTN_WAVES) void cats_tree_attention_kernel(At
     {
         float* po = a.po + slot * D + c4;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) store_coherent16(po + 32 * i, acc[i]);
-        if ((threadIdx.x & 7) == 0) {
+        for (int i = 0; i < NI; ++i) store_coherent16(po + 4 * TPQ * i, acc[i]);
+        if (threadIdx.x % TPQ == 0) {
             __hip_atomic_store(a.pml + slot * 2, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(a.pml + slot * 2 + 1, l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();   // every thread's stores have been acknowledged
-    int* counter = a.arrivals + h * (a.t_pad / 32) + blockIdx.z;
+    int* counter = a.arrivals + h * gridDim.z + blockIdx.z;
     if (threadIdx.x == 0)
         s_last = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.n_chunks - 1;
     __syncthreads();
     if (!s_last) return;
-    // last workgroup of this (head, query group): out = sum_c exp(m_c - M) O_c / sum_c exp(m_c - M) l_c,
-    // chunks in index order, four chunks' loads in flight at a time
+    // last workgroup of this (head, query group): out = sum_c exp2(m_c - M) O_c / sum_c exp2(m_c - M) l_c,
+    // chunks in index order, eight chunks' loads in flight at a time (one memory round trip for
+    // up to eight chunks), rescaled to the running maximum between groups
+    constexpr int MG = 8;
     float Mg = -1e30f;
-    for (int c = 0; c < a.n_chunks; ++c) {
-        const size_t sl = (static_cast<size_t>(h) * a.n_chunks + c) * a.t_pad + qbase + ql;
-        Mg = fmaxf(Mg, __hip_atomic_load(a.pml + sl * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    }
     f32x4 num[NI];
     float den = 0.f;
 #pragma unroll
     for (int i = 0; i < NI; ++i) num[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < a.n_chunks; c0 += 4) {
-        f32x4 v[4][NI];
-        float mc[4], lc[4];
+    for (int c0 = 0; c0 < a.n_chunks; c0 += MG) {
+        f32x4 v[MG][NI];
+        float mc[MG], lc[MG];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < MG; ++j) {
             const int c = min(c0 + j, a.n_chunks - 1);
             const size_t sl = (static_cast<size_t>(h) * a.n_chunks + c) * a.t_pad + qbase + ql;
             mc[j] = __hip_atomic_load(a.pml + sl * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             lc[j] = __hip_atomic_load(a.pml + sl * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const float* po = a.po + sl * D + c4;
 #pragma unroll
-            for (int i = 0; i < NI; ++i) v[j][i] = load_coherent16(po + 32 * i);
+            for (int i = 0; i < NI; ++i) v[j][i] = load_coherent16(po + 4 * TPQ * i);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < MG; ++j)
 #pragma unroll
             for (int i = 0; i < NI; ++i) wait_coherent(v[j][i]);
+        float Mn = Mg;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < MG; ++j) Mn = fmaxf(Mn, mc[j]);   // clamped repeats do not change the maximum
+        const float resc = __builtin_amdgcn_exp2f(Mg - Mn);
+        den *= resc;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) num[i] *= resc;
+        Mg = Mn;
+#pragma unroll
+        for (int j = 0; j < MG; ++j) {
             if (c0 + j < a.n_chunks) {
-                const float wc = __expf(mc[j] - Mg);
+                const float wc = __builtin_amdgcn_exp2f(mc[j] - Mg);
                 den += wc * lc[j];
 #pragma unroll
                 for (int i = 0; i < NI; ++i) num[i] += wc * v[j][i];
@@ -430,9 +481,9 @@ void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st)
 }
 
 void launch_attention(const AttnArgs& a, hipStream_t st) {
-    dim3 grid(a.n_chunks, a.nh, a.t_pad / 32);
+    dim3 grid(a.n_chunks, a.nh, (a.Tq + ATTN_QN - 1) / ATTN_QN);
     if (a.d == 128)
-        hipLaunchKernelGGL(cats_tree_attention_kernel<128>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
+        hipLaunchKernelGGL((cats_tree_attention_kernel<128, ATTN_QN / 16, ATTN_WAVES>), grid, dim3(64 * ATTN_WAVES), 0, st, a);
     else
-        hipLaunchKernelGGL(cats_tree_attention_kernel<64>, grid, dim3(64 * ATTN_WAVES), 0, st, a);
+        hipLaunchKernelGGL((cats_tree_attention_kernel<64, ATTN_QN / 16, ATTN_WAVES>), grid, dim3(64 * ATTN_WAVES), 0, st, a);
 }

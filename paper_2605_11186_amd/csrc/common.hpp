@@ -13,22 +13,20 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
 
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
 
-// round-to-nearest-even; inputs here are always finite
-__device__ __forceinline__ bf16_t f2bf(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return static_cast<bf16_t>(u >> 16);
+// float32 -> bf16, round-to-nearest-even, two values per instruction (v_cvt_pk_bf16_f32 on
+// gfx950); inputs here are always finite
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
-__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
-    return static_cast<uint32_t>(f2bf(lo)) | (static_cast<uint32_t>(f2bf(hi)) << 16);
-}
+__device__ __forceinline__ bf16_t f2bf(float f) { return static_cast<bf16_t>(pack_bf2(f, 0.f) & 0xFFFFu); }
 
 // x ~= hi + lo with hi = bf16(x), lo = bf16(x - hi)
 __device__ __forceinline__ void split_bf2(float a, float b, uint32_t& hi, uint32_t& lo) {
-    const bf16_t ah = f2bf(a), bh = f2bf(b);
-    hi = static_cast<uint32_t>(ah) | (static_cast<uint32_t>(bh) << 16);
-    lo = pack_bf2(a - bf2f(ah), b - bf2f(bh));
+    hi = pack_bf2(a, b);
+    lo = pack_bf2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xFFFF0000u));
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -230,15 +228,22 @@ struct AttnArgs {
     const u32x4* anc;       // device [T] ancestor-or-self masks (cats_tree_masks)
     int T, H, nh, d, max_ctx, ctx_len;   // T: tree nodes whose K/V rows ctx_len.. take part as keys
     int Tq, q0;             // the queries are nodes q0 .. q0+Tq-1 (rows 0..Tq-1 of q / out)
-    int blocks_per_chunk, n_chunks, t_pad;
+    int n_chunks, t_pad;    // key chunks per (head, query group); rows per (head, chunk) in po / pml
     float* po;              // [nh][n_chunks][t_pad][d]
     float* pml;             // [nh][n_chunks][t_pad][2]
-    int* arrivals;          // [nh][t_pad / 32] chunk arrival counters, zero between launches
+    int* arrivals;          // [nh][query groups] chunk arrival counters, zero between launches
     bf16_t* out;            // [Tq][H]
     bf16_t* out_lo;         // optional [Tq][H] low parts of the output
 };
 constexpr int ATTN_KB = 32;    // keys per block
-constexpr int ATTN_WAVES = 4;  // waves per attention workgroup, each taking every 4th block
+// An attention workgroup: ATTN_WAVES waves, each taking every ATTN_WAVES-th key block of the
+// workgroup's chunk for all ATTN_QN queries of the workgroup (two 16-query groups per wave).
+// Measured on the 7B shape (T = 63, S = 1024): eight waves of 16 queries with two chunks take the
+// same 19 us per layer; a single chunk with eight waves 24 us (every wave then walks five blocks
+// one memory round trip after the other).
+constexpr int ATTN_WAVES = 4;
+constexpr int ATTN_QN = 32;
+constexpr int ATTN_MAX_QGROUPS = CATS_MAX_TREE / ATTN_QN;   // query groups per head at most
 void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st);
 void launch_attention(const AttnArgs& a, hipStream_t st);
 void launch_zero_i32(int* p, int n, hipStream_t st);   // fill kernel (a memset node must not enter a captured graph)
