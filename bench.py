@@ -362,23 +362,18 @@ def main():
         ad_arr = cats.layer_array([d_ad])
         kv_model = cats.kv_array(ks[:l_dm], vs[:l_dm])
         kv_ad = cats.kv_array(ks[l_dm:], vs[l_dm:])
-        h = torch.empty(1, dims.hidden, dtype=torch.float32, device=dev)
-        o = torch.empty(1, dims.hidden, dtype=torch.float32, device=dev)
-        amax = torch.empty(1, dtype=torch.int32, device=dev)
-        amax_host = torch.empty(1, dtype=torch.int32).pin_memory()
+
+        toks_dev = torch.empty(g + 1, dtype=torch.int32, device=dev)
+        toks_host = torch.empty(g + 1, dtype=torch.int32).pin_memory()
 
         def draft_cycle():
-            toks = [1]
-            for k in range(g):
-                chain = cats.cats_build_tree(toks[0], toks[1:])
-                cats.cats_set_tree(ctx, *chain[:3], stream)
-                cats.cats_verify_nodes(ctx, layers_arr, 0, l_dm, d_embed, None, kv_model, S, k, h, stream)
-                cats.cats_verify_nodes(ctx, ad_arr, 0, 1, None, h, kv_ad, S, k, o, stream)
-                cats.cats_lm_head_argmax(ctx, o, g_out, d_final["w_lm"], amax, stream=stream)
-                amax_host.copy_(amax, non_blocking=True)
-                torch.cuda.synchronize()
-                toks.append(int(amax_host[0]))
-            return toks
+            # the chain grows on the device: the argmax of step k is the embedding row of step k + 1;
+            # one read-back per gamma tokens
+            cats.cats_draft_chain(ctx, layers_arr, 0, l_dm, ad_arr, g_out, d_final["w_lm"], d_embed, kv_model,
+                                  kv_ad, S, 1, g, toks_dev, stream=stream)
+            toks_host.copy_(toks_dev, non_blocking=True)
+            torch.cuda.synchronize()
+            return toks_host.tolist()
 
         for _ in range(args.warmup):
             draft_cycle()
@@ -398,7 +393,7 @@ def main():
                                      "ctx_len": S, "seed": seed, "drafted": toks[1:]},
                           "draft": {"us_per_token": round(ms_cycle * 1e3 / g, 1), "weight_bytes_per_token": w_tok,
                                     "weight_gbs": round(w_tok * g / (ms_cycle * 1e-3) / 1e9, 1),
-                                    "note": "every token ends with a host read-back of the drafted id"}}))
+                                    "note": "cats_draft_chain: tokens stay on the device, one host read-back per gamma tokens"}}))
         return
 
     if cascade:
@@ -459,13 +454,21 @@ def main():
         del src, dst
     for _ in range(args.warmup):
         step()
+    # K timed steps between two synchronisations; an event on the launch stream after every step
+    # gives the per-step durations, whose median is the reported step time (the wall-clock mean
+    # over the same region is kept beside it)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed / args.steps * 1e3
+    per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)])
+    ms_wall_mean = elapsed / args.steps * 1e3
+    ms_per_step = float(np.median(per_step))
     accepted = cats.accept_result_from_tensor(res_dev)
 
     # Same K steps again with HIP events around every GEMM launch (on the launch stream): the
@@ -487,13 +490,16 @@ def main():
     gemm_gbs = gemm_bytes_per_launch / gemm_avg_s / 1e9
     step_gbs = (w_bytes + kv_bytes) / (ms_per_step * 1e-3) / 1e9
 
-    # HBM traffic per GEMM launch from the committed rocprofv3 --pmc summary of this same workload
-    traffic = None
-    prof = ROOT / "profiles" / f"cats_gemm_{args.workload}.pmc.txt"
+    # HBM traffic (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size) is not
+    # measured in this run: it is read from the committed summary of this same workload
+    traffic, step_traffic = None, None
+    prof = ROOT / "profiles" / f"verify_step_{args.workload}.pmc.txt"
     if prof.exists() and not args.tree_nodes and not args.ctx:
         for line in prof.read_text().splitlines():
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith("gemm_traffic_bytes_per_launch:"):
                 traffic = int(line.split(":")[1])
+            if line.startswith("step_traffic_bytes:"):
+                step_traffic = int(line.split(":")[1])
 
     out = {
         "metric": "tree-verify steps/sec",
@@ -514,11 +520,18 @@ def main():
                        accepted["n_accepted"] == int(golden["n_accepted"][0])
                        and accepted["path"] == [int(v) for v in golden["path"]]
                        and accepted["bonus_token"] == int(golden["bonus_token"][0]))},
+        "timing": {"value_is": "1 / median of the per-step times (events on the launch stream between steps)",
+                   "median_ms": round(ms_per_step, 4), "wall_mean_ms": round(ms_wall_mean, 4),
+                   "min_ms": round(float(per_step.min()), 4), "max_ms": round(float(per_step.max()), 4)},
         "step_hbm": {"algorithmic_bytes": w_bytes + kv_bytes, "weight_bytes": w_bytes, "kv_bytes": kv_bytes,
-                     "achieved_gbs": round(step_gbs, 1), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
+                     "achieved_gbs": round(step_gbs, 1), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": step_traffic,
+                     "traffic_over_algorithmic": None if step_traffic is None else round(step_traffic / (w_bytes + kv_bytes), 3),
+                     "traffic_source": None if step_traffic is None else f"profiles/{prof.name} (committed rocprofv3 --pmc summary, all kernels of one step)"},
         "roofline": {"bound": "hbm", "kernel": cats.cats_gemm_kernel_name(),
                      "achieved": round(gemm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gemm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_source": None if traffic is None else f"profiles/{prof.name} (committed rocprofv3 --pmc summary)",
                      "launches_per_step": gemm_launches // args.steps,
                      "avg_launch_us": round(gemm_avg_s * 1e6, 2),
                      "bytes_per_launch": int(gemm_bytes_per_launch)},

@@ -213,6 +213,28 @@ int cats_verify_nodes(cats_ctx *ctx, const cats_layer_weights *layers, int32_t l
                       const cats_kv_layer *kv, int32_t ctx_len, int32_t node_begin,
                       float *hidden_out, void *stream);
 
+/* Drafting stage on the device (Sec. 3.2, draft stage; Alg. 1, stage 1: gamma sequential passes
+ * through the draft layers, the draft adapter and the shared LM head, y = argmax H(o)).  The chain
+ * root, d_1 .. d_gamma becomes the context's tree; step k forwards node k alone through layers
+ * [layer_begin, layer_end) of `layers` (its K/V at cache row ctx_len + k of kv), then through the
+ * attention-only block `adapter` (cache kv_adapter, one layer), applies RMSNorm with g_adapter_out
+ * and the LM head w_lm, and writes the argmax as the token of node k + 1 ON THE DEVICE, where
+ * step k + 1 reads it for its embedding row: no host round trip between the tokens.
+ * layers, kv: HOST arrays indexed by layer (kv_adapter: HOST pointer to one cats_kv_layer);
+ * embed, g_adapter_out, w_lm: DEVICE.  Outputs (DEVICE): tokens_out int32 [gamma + 1] = root and
+ * the gamma drafted tokens; hidden_out float32 [gamma + 1][hidden], optional: every chain node's
+ * residual stream after layer layer_end - 1 (what the shallow-verification stage continues from;
+ * when given, the last draft takes one more pass through the draft layers, without the adapter).
+ * Afterwards the context's tree is that chain (cats_verify_nodes can continue on it).
+ * CATS_EINVAL: gamma outside [1, CATS_MAX_DEPTH] or gamma + 1 > max_tree, empty layer range,
+ * adapter with feed-forward matrices, root token out of range; CATS_ECAPACITY: ctx_len + gamma + 1
+ * > max_ctx. */
+int cats_draft_chain(cats_ctx *ctx, const cats_layer_weights *layers, int32_t layer_begin,
+                     int32_t layer_end, const cats_layer_weights *adapter, const void *g_adapter_out,
+                     const void *w_lm, const void *embed, const cats_kv_layer *kv,
+                     const cats_kv_layer *kv_adapter, int32_t ctx_len, int32_t root_token,
+                     int32_t gamma, int32_t *tokens_out, float *hidden_out, void *stream);
+
 /* Verification tree of one cascaded cycle (Alg. 1, stage 2: ChainTree / BuildTree; Fig. 4 right
  * upper).  HOST arrays only, nothing is enqueued.  Node 0 carries root_token (the last committed
  * token); draft position i (token main_tokens[i], i < gamma) is node i + 1, child of node i; every

@@ -15,7 +15,7 @@ __all__ = ["CATS_MAX_TREE", "CATS_MAX_DEPTH", "CatsError", "ModelDesc", "LayerWe
            "AcceptResult", "library", "library_path", "exported_symbols", "cats_create",
            "cats_destroy", "cats_set_tree", "cats_verify_layer", "cats_tree_attention", "cats_tree_attention_noalloc",
            "CATS_NOALLOC_SCRATCH_BYTES",
-           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_reduced_kl_loss", "cats_set_acceptance",
+           "cats_accept_and_compact", "cats_verify_tree", "cats_verify_nodes", "cats_build_tree", "cats_draft_chain", "cats_reduced_kl_loss", "cats_set_acceptance",
            "cats_typical_stats", "cats_compact_along", "CATS_LOSS_MAX_K", "CATS_LOSS_MAX_VOCAB",
            "cats_lm_head_argmax",
            "cats_gemm_kernel_name", "cats_strerror", "cats_profile_gemm", "cats_profile_gemm_read",
@@ -104,6 +104,9 @@ _SIGNATURES = {
     "cats_profile_gemm_read": [C.c_void_p, C.c_void_p, C.c_void_p],
     "cats_lm_head_argmax": [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                             C.c_void_p, C.c_void_p, C.c_void_p],
+    "cats_draft_chain": [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                         C.c_void_p, C.c_void_p],
     "cats_tree_attention_noalloc": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p],
 }
@@ -242,6 +245,16 @@ def cats_verify_nodes(ctx, layers_arr, layer_begin: int, layer_end: int, embed, 
     _check(library().cats_verify_nodes(
         ctx, layers_arr, int(layer_begin), int(layer_end), _dp(embed), _dp(hidden_in), kv_arr,
         int(ctx_len), int(node_begin), _dp(hidden_out), _stream(stream)))
+
+
+def cats_draft_chain(ctx, layers_arr, layer_begin: int, layer_end: int, adapter_arr, g_adapter_out, w_lm,
+                     embed, kv_arr, kv_adapter_arr, ctx_len: int, root_token: int, gamma: int, tokens_out,
+                     hidden_out=None, stream=None):
+    """Stage-1 draft loop on the device; adapter_arr / kv_adapter_arr are one-element arrays."""
+    _check(library().cats_draft_chain(
+        ctx, layers_arr, int(layer_begin), int(layer_end), adapter_arr, _dp(g_adapter_out), _dp(w_lm),
+        _dp(embed), kv_arr, kv_adapter_arr, int(ctx_len), int(root_token), int(gamma), _dp(tokens_out),
+        _dp(hidden_out), _stream(stream)))
 
 
 def cats_build_tree(root_token: int, main_tokens, corrections=None, capacity: int = CATS_MAX_TREE):

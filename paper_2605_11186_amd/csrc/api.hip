@@ -176,7 +176,7 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     a.kc = static_cast<const bf16_t*>(kv->k);
     a.vt = static_cast<const bf16_t*>(kv->v);
     a.anc = c->anc;
-    a.T = c->T;
+    a.T = c->n0 + c->rows;   // keys: the tree rows up to the call's last node (later rows may not exist yet)
     a.Tq = c->rows;
     a.q0 = c->n0;
     a.H = c->d.hidden;
@@ -704,6 +704,72 @@ int cats_verify_nodes(cats_ctx* ctx, const cats_layer_weights* layers, int32_t l
     const size_t bytes = sizeof(float) * static_cast<size_t>(ctx->T - node_begin) * ctx->d.hidden;
     HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, bytes, hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipGetLastError());
+    return CATS_OK;
+}
+
+int cats_draft_chain(cats_ctx* ctx, const cats_layer_weights* layers, int32_t layer_begin, int32_t layer_end,
+                     const cats_layer_weights* adapter, const void* g_adapter_out, const void* w_lm,
+                     const void* embed, const cats_kv_layer* kv, const cats_kv_layer* kv_adapter, int32_t ctx_len,
+                     int32_t root_token, int32_t gamma, int32_t* tokens_out, float* hidden_out, void* stream) {
+    if (!ctx || !adapter || !g_adapter_out || !w_lm || !embed || !tokens_out) return CATS_EINVAL;
+    if (gamma < 1 || gamma > CATS_MAX_DEPTH || gamma + 1 > ctx->d.max_tree) return CATS_EINVAL;
+    if (root_token < 0 || root_token >= ctx->d.vocab || ctx_len < 0) return CATS_EINVAL;
+    if (static_cast<int64_t>(ctx_len) + gamma + 1 > ctx->d.max_ctx) return CATS_ECAPACITY;
+    int rc = check_layer_range(ctx, layers, layer_begin, layer_end, kv);
+    if (rc != CATS_OK) return rc;
+    if (layer_end <= layer_begin) return CATS_EINVAL;
+    if (!layer_ok(adapter) || has_ffn(adapter) || !kv_ok(kv_adapter, 0, 1)) return CATS_EINVAL;
+    hipStream_t st = as_stream(stream);
+    // the chain root, d_1 .. d_gamma as the context's tree; the draft tokens are filled in on
+    // the device as they are produced
+    const int n = gamma + 1;
+    TreeUploadArgs up;
+    std::memset(&up, 0, sizeof up);
+    up.token[0] = root_token;
+    for (int i = 0; i < n; ++i) {
+        up.parent[i] = i - 1;
+        up.depth[i] = i;
+        ctx->h_parent[i] = i - 1;
+        ctx->h_depth[i] = i;
+    }
+    launch_tree_upload(up, n, ctx->token, ctx->parent, ctx->depth, st);
+    launch_tree_masks(ctx->parent, n, ctx->anc, st);
+    ctx->T = n;
+    enqueue_rope_table(ctx, ctx_len, st);
+    const size_t H = ctx->d.hidden;
+    for (int k = 0; k <= gamma; ++k) {
+        if (k == gamma && !hidden_out) break;   // the last draft only needs its hidden state
+        ctx->n0 = k;
+        ctx->rows = 1;
+        ResidualNormArgs rn;
+        rn.x = ctx->x;
+        rn.x_in = nullptr;
+        rn.embed = static_cast<const bf16_t*>(embed);
+        rn.token = ctx->token + k;
+        rn.part = nullptr;
+        rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
+        rn.gain = static_cast<const bf16_t*>(layers[layer_begin].g_attn);
+        rn.xn = ctx->xn;
+        rn.xn_lo = ctx->xn_lo;
+        rn.ss = ctx->ss;
+        rn.T = 1;
+        rn.H = ctx->d.hidden;
+        rn.eps = ctx->d.rms_eps;
+        launch_residual_norm(rn, st);
+        for (int l = layer_begin; l < layer_end; ++l) {
+            const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : adapter->g_attn;
+            enqueue_layer(ctx, &layers[l], ctx->x, &kv[l], ctx_len, next_gain, st);
+        }
+        if (hidden_out)
+            HIP_TRY(hipMemcpyAsync(hidden_out + k * H, ctx->x, sizeof(float) * H, hipMemcpyDeviceToDevice, st));
+        if (k == gamma) break;
+        enqueue_layer(ctx, adapter, ctx->x, kv_adapter, ctx_len, g_adapter_out, st);
+        enqueue_lm_head(ctx, w_lm, nullptr, ctx->token + k + 1, nullptr, st);
+    }
+    HIP_TRY(hipMemcpyAsync(tokens_out, ctx->token, sizeof(int32_t) * n, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipGetLastError());
+    ctx->n0 = 0;
+    ctx->rows = n;
     return CATS_OK;
 }
 

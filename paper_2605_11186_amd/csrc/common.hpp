@@ -83,21 +83,42 @@ GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc = GEMM_KC);
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
-// Sum of `pieces` 16-byte groups p[s * stride] (fixed order).  Loads go out in batches of eight
-// independent loads (indices past the end are clamped and masked), so a reader waits for one
-// memory round trip per batch instead of one per piece.
-__device__ __forceinline__ f32x4 sum_pieces4(const float* p, size_t stride, int pieces) {
-    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < pieces; s0 += 8) {
-        f32x4 v[8];
+// Sums of the pieces of G 16-byte groups at once: acc[g] = sum over s < pieces[g] of
+// p[g][s * stride], each in index order (deterministic).  The loads of all G groups go out
+// together in batches of B pieces (indices past a group's end are clamped and masked), so a
+// reader waits for one memory round trip per batch, not one per piece or per group.
+template <int G, int B>
+__device__ __forceinline__ void sum_pieces4_multi(const float* const (&p)[G], size_t stride, const int (&pieces)[G],
+                                                  f32x4 (&acc)[G]) {
+    int most = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            v[i] = *reinterpret_cast<const f32x4*>(p + static_cast<size_t>(min(s0 + i, pieces - 1)) * stride);
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (s0 + i < pieces) acc += v[i];
+    for (int g = 0; g < G; ++g) {
+        acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        most = max(most, pieces[g]);
     }
-    return acc;
+    for (int s0 = 0; s0 < most; s0 += B) {
+        f32x4 v[G][B];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < B; ++i)
+                v[g][i] = *reinterpret_cast<const f32x4*>(p[g] + static_cast<size_t>(min(s0 + i, pieces[g] - 1)) * stride);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < B; ++i)
+                if (s0 + i < pieces[g]) acc[g] += v[g][i];
+    }
+}
+
+// Sum of `pieces` 16-byte groups p[s * stride] (fixed order), B loads in flight.
+template <int B = 8>
+__device__ __forceinline__ f32x4 sum_pieces4(const float* p, size_t stride, int pieces) {
+    const float* const pp[1] = {p};
+    const int np[1] = {pieces};
+    f32x4 acc[1];
+    sum_pieces4_multi<1, B>(pp, stride, np, acc);
+    return acc[0];
 }
 
 // Sum of the pieces of column n of row t (fixed order).

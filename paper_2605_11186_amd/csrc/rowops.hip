@@ -32,7 +32,7 @@ __global__ __launch_bounds__(64) void cats_residual_rmsnorm(ResidualNormArgs a) 
             val = *reinterpret_cast<const f32x4*>((a.x_in ? a.x_in : a.x) + row + j);
         }
         if (a.part) {
-            val += sum_pieces4(a.part + row + j, static_cast<size_t>(a.T) * a.H, plan_pieces(a.plan, j / a.plan.bn));
+            val += sum_pieces4<16>(a.part + row + j, static_cast<size_t>(a.T) * a.H, plan_pieces(a.plan, j / a.plan.bn));
         }
         ss = val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
         if (a.embed || a.x_in || a.part) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
@@ -89,10 +89,13 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         for (int t0 = 0; t0 < a.T; t0 += 64) {   // two nodes per thread and pass
             const int ta = t0 + (threadIdx.x >> 3), tb = ta + 32;
             const int ca = min(ta, a.T - 1), cb = min(tb, a.T - 1);
-            f32x4 va = sum_pieces4(a.part + static_cast<size_t>(ca) * N + col, stride, pieces);
-            f32x4 vb4 = sum_pieces4(a.part + static_cast<size_t>(cb) * N + col, stride, pieces);
-            va *= row_scale(a.ns, ca);
-            vb4 *= row_scale(a.ns, cb);
+            const float* const pv[2] = {a.part + static_cast<size_t>(ca) * N + col,
+                                        a.part + static_cast<size_t>(cb) * N + col};
+            const int npv[2] = {pieces, pieces};
+            f32x4 sv[2];
+            sum_pieces4_multi<2, 8>(pv, stride, npv, sv);
+            f32x4 va = sv[0] * row_scale(a.ns, ca);
+            f32x4 vb4 = sv[1] * row_scale(a.ns, cb);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bf16_t ha = f2bf(va[e]), hb = f2bf(vb4[e]);
@@ -124,13 +127,12 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
     const int c0 = h * a.d + j;
     // the column groups of one head lie in different row tiles; within a head all columns
     // share a tile (head_dim divides the tile height)
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const int col = m * a.H + c0;
-        const int pieces = plan_pieces(a.plan, col / a.plan.bn);
-        const float* p = a.part + static_cast<size_t>(t) * N + col;
-        v4[2 * m] = sum_pieces4(p, stride, pieces);
-        v4[2 * m + 1] = sum_pieces4(p + half, stride, pieces);
+    {
+        const float* pq = a.part + static_cast<size_t>(t) * N + c0;
+        const float* const pp[4] = {pq, pq + half, pq + a.H, pq + a.H + half};
+        const int nq = plan_pieces(a.plan, c0 / a.plan.bn), nk = plan_pieces(a.plan, (a.H + c0) / a.plan.bn);
+        const int np[4] = {nq, nq, nk, nk};
+        sum_pieces4_multi<4, 8>(pp, stride, np, v4);
     }
     const float rs = row_scale(a.ns, t);
 #pragma unroll
@@ -177,8 +179,11 @@ __global__ void cats_swiglu(SwigluArgs a) {
     const size_t stride = static_cast<size_t>(a.T) * N;
     const float* p = a.part + static_cast<size_t>(t) * N + n;
     // n % 4 == 0 and the tile height is a multiple of 4: the four columns share a tile
-    f32x4 gt = sum_pieces4(p, stride, plan_pieces(a.plan, n / a.plan.bn));
-    f32x4 up = sum_pieces4(p + a.f_pad, stride, plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn));
+    const float* const pp[2] = {p, p + a.f_pad};
+    const int np[2] = {plan_pieces(a.plan, n / a.plan.bn), plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn)};
+    f32x4 gu[2];
+    sum_pieces4_multi<2, 4>(pp, stride, np, gu);
+    f32x4 gt = gu[0], up = gu[1];
     const float rs = row_scale(a.ns, t);
     gt *= rs;
     up *= rs;

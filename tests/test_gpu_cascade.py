@@ -218,6 +218,15 @@ def test_whole_cycle_with_synthetic_adapters(tiny4):
     assert g_tokens == o_tokens
     assert rel_err(h_dm.cpu().numpy(), o_hdm) <= REL_TOL
     drafts = np.array(g_tokens[1:], dtype=np.int32)
+    # the same stage in one call, the chain growing on the device (no read-back between tokens):
+    # same kernels on the same rows, so tokens and hidden states must be identical
+    toks_dev = torch.full((gamma + 1,), -1, dtype=torch.int32, device="cuda")
+    h_dev = torch.zeros(gamma + 1, H, dtype=torch.float32, device="cuda")
+    cats.cats_draft_chain(p.ctx, p.layers_arr, 0, L_DM, ad_arr[0], d_gout[0], p.d_final["w_lm"], p.d_embed,
+                          kv_target, ad_kv[0], S, root, gamma, toks_dev, hidden_out=h_dev)
+    torch.cuda.synchronize()
+    assert toks_dev.cpu().tolist() == g_tokens
+    assert torch.equal(h_dev, h_dm)
 
     # ---- stage 2: shallow layers on all chain positions in parallel, verifier adapter, corrections
     chain = cats.cats_build_tree(root, drafts)
