@@ -45,11 +45,14 @@ struct GemmPlan {
     int n_wgs;   // workgroups
     int items;   // tiles * chunks
 };
+// 32-bit unsigned arithmetic (a 64-bit division costs a few hundred scalar instructions on the
+// device, at the head of every launch): make_gemm_plan guarantees items * n_wgs < 2^31.
 __host__ __device__ inline int plan_owner(const GemmPlan& p, int item) {
-    return static_cast<int>((static_cast<long long>(item + 1) * p.n_wgs - 1) / p.items);
+    return static_cast<int>((static_cast<unsigned>(item + 1) * static_cast<unsigned>(p.n_wgs) - 1u) /
+                            static_cast<unsigned>(p.items));
 }
 __host__ __device__ inline int plan_item_begin(const GemmPlan& p, int wg) {
-    return static_cast<int>(static_cast<long long>(wg) * p.items / p.n_wgs);
+    return static_cast<int>(static_cast<unsigned>(wg) * static_cast<unsigned>(p.items) / static_cast<unsigned>(p.n_wgs));
 }
 __host__ __device__ inline int plan_first_wg(const GemmPlan& p, int tile) { return plan_owner(p, tile * p.chunks); }
 __host__ __device__ inline int plan_pieces(const GemmPlan& p, int tile) {

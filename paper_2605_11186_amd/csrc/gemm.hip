@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs 
     // item (local index i) -> tile and first k of its chunk
 #define CATS_ITEM(i, tile_, k0_)                  \
     const int gi_ = item_lo + (i);                \
-    const int tile_ = gi_ / C;                    \
+    const int tile_ = static_cast<int>(static_cast<unsigned>(gi_) / static_cast<unsigned>(C)); \
     const int k0_ = (gi_ - tile_ * C) * KC;
 
 #define CATS_LOAD_X(i)                                                                              \
@@ -190,7 +190,11 @@ __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs 
                 _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                   \
                     _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                \
                     const int t = tb * 32 + 8 * (r >> 2) + 4 * g_here + (r & 3);            \
-                    if (t < a.T) out[static_cast<size_t>(t) * a.N] = acc[tb][r];                    \
+                    /* write-through store: the partial tile goes on to memory at once instead   */ \
+                    /* of waiting, dirty, in the XCD's L2 for the write-back at the kernel's end */ \
+                    if (t < a.T)                                                                    \
+                        __hip_atomic_store(out + static_cast<size_t>(t) * a.N, acc[tb][r], __ATOMIC_RELAXED, \
+                                           __HIP_MEMORY_SCOPE_AGENT);                               \
                 }                                                                                   \
             }                                                                                       \
             _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                       \
@@ -286,6 +290,9 @@ GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc) {
     p.chunks = (K + kc - 1) / kc;
     const int tiles = (N + bn - 1) / bn;
     p.items = tiles * p.chunks;
+    // the device-side plan arithmetic is 32-bit: items * workgroups stays far below 2^31 for every
+    // supported shape (at most 128 Ki rows x 8 Ki columns per product)
+    if (static_cast<long long>(p.items) * target_wgs >= (1ll << 31)) target_wgs = static_cast<int>((1ll << 31) / p.items) - 1;
     if (target_wgs >= p.items) {
         p.n_wgs = p.items;
         return p;

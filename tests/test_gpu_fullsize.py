@@ -38,7 +38,7 @@ def run_step(pair, ks, vs, S, tok, parent, depth):
     return hidden.cpu().numpy(), logits.cpu().numpy(), amax.cpu().numpy(), host.as_dict()
 
 
-def compare_with_oracle(pair, S, tok, parent, depth, kv_seed, check_paths=()):
+def compare_with_oracle(pair, S, tok, parent, depth, kv_seed, check_paths=(), guard=None):
     kc, vc = pair.oracle_cache_random(kv_seed, S)
     ks, vs = pair.device_cache_from_oracle(kc, vc, S)
     g_hidden, g_logits, g_amax, g_acc = run_step(pair, ks, vs, S, tok, parent, depth)
@@ -67,6 +67,8 @@ def compare_with_oracle(pair, S, tok, parent, depth, kv_seed, check_paths=()):
     print(f"element-wise where |ref| > 1e-3 max|ref|: hidden {fmt_elementwise(rel_err_elementwise(g_hidden, o_hidden))}; "
           f"logits {fmt_elementwise(rel_err_elementwise(g_logits, o_logits))}")
     assert e_h <= REL_TOL and e_l <= REL_TOL
+    if guard is not None:   # regression guard, far inside the tolerance (see the caller)
+        assert e_h <= guard and e_l <= guard, (e_h, e_l, guard)
     safe = o_margin > MARGIN
     assert np.array_equal(g_amax[safe], o_amax[safe])
     assert g_acc == pair.oracle.accept(tok, parent, depth, g_amax, S)
@@ -100,7 +102,11 @@ def test_7b_full_verify_step_matches_oracle():
     pair = Pair(dims, BENCH_SEED, max_ctx=(S + T + 63) // 64 * 64, max_tree=T, precision="f32", packed=True)
     try:
         path = [int(v) for v in golden["path"]]
-        acc = compare_with_oracle(pair, S, tok, parent, depth, BENCH_SEED, check_paths=(0, path[-1]))
+        # The tolerance of the contract is REL_TOL.  Measured here: 7e-5, because inside a step the
+        # tree's own K/V rows keep their low parts; with those rows rounded to bf16 the same step
+        # measures 1e-2.  The guard at 2e-3 fails if that path (or the high + low split of the
+        # GEMM inputs, which costs about as much) stops working, long before REL_TOL would.
+        acc = compare_with_oracle(pair, S, tok, parent, depth, BENCH_SEED, check_paths=(0, path[-1]), guard=2e-3)
         # the stored expectation (every decision on the accepted path has a margin > 4e-2)
         assert float(golden["min_margin_on_path"][0]) > MARGIN
         assert acc["n_accepted"] == int(golden["n_accepted"][0]) == 4

@@ -135,6 +135,17 @@ def test_verify_tree_ragged_context_lengths(tiny, S):
     check_step(tiny, kc, vc, ks, vs, S, tok, parent, depth)
 
 
+@pytest.mark.parametrize("S", [31, 63, 95])
+def test_largest_tree_behind_a_context_that_ends_a_key_block(tiny, S):
+    """128 nodes whose first row is the last key of a 32-key block: the tree spans five key blocks
+    and the low-part window beside the cache is used up to its last row."""
+    parent, depth = synth.random_tree(128, 16, S)
+    tok = synth.distinct_sibling_tokens(parent, synth.TINY.vocab, S)
+    kc, vc = tiny.oracle_cache_random(SEED + S, S)
+    ks, vs = tiny.device_cache_from_oracle(kc, vc, S)
+    check_step(tiny, kc, vc, ks, vs, S, tok, parent, depth)
+
+
 def test_accepting_drafts_are_accepted(tiny):
     """A tree whose main chain follows the oracle's greedy continuation is accepted to the end,
     and wrong siblings are not."""
