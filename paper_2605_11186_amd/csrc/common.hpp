@@ -146,15 +146,28 @@ struct NormScale {
     float eps;
 };
 // Entries past n_ss are never written and stay zero, so the whole row of SS_STRIDE floats is
-// added up with eight independent 16-byte loads (fixed order: deterministic).
-__device__ __forceinline__ float row_scale(const NormScale& ns, int t) {
+// added up with eight independent 16-byte loads (fixed order: deterministic).  In two halves, so
+// that a kernel can request the row before its partial-sum loads and use it after them: one
+// memory round trip instead of two.
+struct RowSquares {
+    f32x4 v[SS_STRIDE / 4];
+};
+__device__ __forceinline__ RowSquares row_squares_load(const NormScale& ns, int t) {
     const f32x4* p = reinterpret_cast<const f32x4*>(ns.ss + t * SS_STRIDE);
-    f32x4 acc = p[0];
+    RowSquares r;
 #pragma unroll
-    for (int b = 1; b < SS_STRIDE / 4; ++b) acc += p[b];
+    for (int b = 0; b < SS_STRIDE / 4; ++b) r.v[b] = p[b];
+    __builtin_amdgcn_sched_barrier(0);   // keep the requests ahead of what follows
+    return r;
+}
+__device__ __forceinline__ float row_scale(const NormScale& ns, const RowSquares& r) {
+    f32x4 acc = r.v[0];
+#pragma unroll
+    for (int b = 1; b < SS_STRIDE / 4; ++b) acc += r.v[b];
     const float tot = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     return 1.0f / sqrtf(tot / static_cast<float>(ns.H) + ns.eps);
 }
+__device__ __forceinline__ float row_scale(const NormScale& ns, int t) { return row_scale(ns, row_squares_load(ns, t)); }
 
 struct ResidualNormArgs {
     float* x;               // [T][H] residual stream, in/out

@@ -89,13 +89,14 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         for (int t0 = 0; t0 < a.T; t0 += 64) {   // two nodes per thread and pass
             const int ta = t0 + (threadIdx.x >> 3), tb = ta + 32;
             const int ca = min(ta, a.T - 1), cb = min(tb, a.T - 1);
+            const RowSquares sqa = row_squares_load(a.ns, ca), sqb = row_squares_load(a.ns, cb);
             const float* const pv[2] = {a.part + static_cast<size_t>(ca) * N + col,
                                         a.part + static_cast<size_t>(cb) * N + col};
             const int npv[2] = {pieces, pieces};
             f32x4 sv[2];
             sum_pieces4_multi<2, 8>(pv, stride, npv, sv);
-            f32x4 va = sv[0] * row_scale(a.ns, ca);
-            f32x4 vb4 = sv[1] * row_scale(a.ns, cb);
+            f32x4 va = sv[0] * row_scale(a.ns, sqa);
+            f32x4 vb4 = sv[1] * row_scale(a.ns, sqb);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const bf16_t ha = f2bf(va[e]), hb = f2bf(vb4[e]);
@@ -127,6 +128,7 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
     const int c0 = h * a.d + j;
     // the column groups of one head lie in different row tiles; within a head all columns
     // share a tile (head_dim divides the tile height)
+    const RowSquares sq = row_squares_load(a.ns, t);
     {
         const float* pq = a.part + static_cast<size_t>(t) * N + c0;
         const float* const pp[4] = {pq, pq + half, pq + a.H, pq + a.H + half};
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(256) void cats_qkv_rope_append(QkvRopeArgs a) {
         const int np[4] = {nq, nq, nk, nk};
         sum_pieces4_multi<4, 8>(pp, stride, np, v4);
     }
-    const float rs = row_scale(a.ns, t);
+    const float rs = row_scale(a.ns, sq);
 #pragma unroll
     for (int m = 0; m < 4; ++m) v4[m] *= rs;
     const size_t qo = static_cast<size_t>(t) * a.H + c0;
@@ -179,12 +181,13 @@ __global__ void cats_swiglu(SwigluArgs a) {
     const size_t stride = static_cast<size_t>(a.T) * N;
     const float* p = a.part + static_cast<size_t>(t) * N + n;
     // n % 4 == 0 and the tile height is a multiple of 4: the four columns share a tile
+    const RowSquares sq = row_squares_load(a.ns, t);
     const float* const pp[2] = {p, p + a.f_pad};
     const int np[2] = {plan_pieces(a.plan, n / a.plan.bn), plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn)};
     f32x4 gu[2];
     sum_pieces4_multi<2, 4>(pp, stride, np, gu);
     f32x4 gt = gu[0], up = gu[1];
-    const float rs = row_scale(a.ns, t);
+    const float rs = row_scale(a.ns, sq);
     gt *= rs;
     up *= rs;
     float hv[4];
