@@ -79,7 +79,10 @@ typedef struct {
 /* One layer's KV cache, bf16.  k: [n_heads][max_ctx][head_dim], keys stored after
  * rotation.  v: [n_heads][head_dim][max_ctx], i.e. values stored TRANSPOSED so
  * that the row (context) index is the contiguous one.  Rows [0, ctx_len) are the
- * committed context; a verify call writes rows ctx_len .. ctx_len+T-1. */
+ * committed context; a verify call writes rows ctx_len .. ctx_len+T-1.  The cache is what is
+ * kept between calls and its precision is bf16; within one call the rows that the call itself
+ * appends also take part in attention with their rounding remainders (kept in the context's
+ * scratch), i.e. at about 16 mantissa bits. */
 typedef struct {
     void *k, *v;
 } cats_kv_layer;

@@ -290,3 +290,37 @@ def test_attention_only_block_argument_rules(tiny4):
     with pytest.raises(cats.CatsError) as e:
         cats.cats_verify_nodes(p.ctx, cats.layer_array([half]), 0, 1, p.d_embed, None, kv_arr, 8, 0, out)
     assert e.value.status == cats.CATS_EINVAL
+
+
+def test_draft_chain_argument_rules(tiny4):
+    """Host-side validation of cats_draft_chain: nothing is enqueued for a bad call."""
+    p = tiny4
+    d = p.dims
+    from gpu_common import to_dev_bf16
+    ad = synth.adapter_weights(d, 7, 0)
+    d_ad = cats.pack_layer({k: to_dev_bf16(v) for k, v in ad.items() if k != "g_out"})
+    g_out = to_dev_bf16(ad["g_out"])
+    ad_arr = cats.layer_array([d_ad])
+    ks = [torch.zeros(d.n_heads, p.max_ctx, d.head_dim, dtype=torch.bfloat16, device="cuda") for _ in range(p.L + 1)]
+    vs = [torch.zeros(d.n_heads, d.head_dim, p.max_ctx, dtype=torch.bfloat16, device="cuda") for _ in range(p.L + 1)]
+    kv, kv_ad = cats.kv_array(ks[:p.L], vs[:p.L]), cats.kv_array(ks[p.L:], vs[p.L:])
+    toks = torch.zeros(32, dtype=torch.int32, device="cuda")
+
+    def status(**kw):
+        a = dict(layer_begin=0, layer_end=1, adapter=ad_arr, ctx_len=10, root=3, gamma=4)
+        a.update(kw)
+        try:
+            cats.cats_draft_chain(p.ctx, p.layers_arr, a["layer_begin"], a["layer_end"], a["adapter"], g_out,
+                                  p.d_final["w_lm"], p.d_embed, kv, kv_ad, a["ctx_len"], a["root"], a["gamma"], toks)
+        except cats.CatsError as e:
+            return e.status
+        return cats.CATS_OK
+
+    assert status(gamma=0) == cats.CATS_EINVAL
+    assert status(gamma=cats.CATS_MAX_DEPTH + 1) == cats.CATS_EINVAL
+    assert status(root=d.vocab) == cats.CATS_EINVAL
+    assert status(layer_end=0) == cats.CATS_EINVAL                      # empty layer range
+    assert status(adapter=p.layers_arr) == cats.CATS_EINVAL             # a full layer is not an adapter block
+    assert status(ctx_len=p.max_ctx - 3) == cats.CATS_ECAPACITY
+    assert status() == cats.CATS_OK
+    torch.cuda.synchronize()
