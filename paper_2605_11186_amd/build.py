@@ -7,7 +7,7 @@ from pathlib import Path
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
 LIB = PKG / "libcats.so"
-SOURCES = ["gemm.hip", "rowops.hip", "attention.hip", "accept.hip", "loss.hip", "api.hip"]
+SOURCES = ["gemm.hip", "gemv.hip", "rowops.hip", "attention.hip", "accept.hip", "loss.hip", "api.hip"]
 
 
 def build_library(verbose: bool = False) -> Path:

@@ -36,6 +36,19 @@ struct cats_ctx {
     bf16_t *hact, *hact_lo;  // [max_tree][F] SwiGLU output
     float* part;     // split-K partial sums
     size_t part_elems;
+    // Single-row calls (rows == 1) run on cats_gemv_row, which folds the residual / norm and SwiGLU
+    // steps into the product behind them.  Between two products the row is therefore (x, pend):
+    // the residual row as of its last update and the partial sums of the last product, still to be
+    // added.  Products alternate between two partial-sum buffers (a product reads the one before
+    // while it writes its own) and residual updates between two rows.
+    struct {
+        float* x;               // the residual row as of its last update
+        const float* pend;      // [pieces][hidden] partial sums still to be added to it; null: none
+        GemmPlan pend_plan;
+        const void* next_gain;  // gain of the norm that follows the pending update (LM head)
+    } row = {nullptr, nullptr, {}, nullptr};
+    float* x_row;     // [hidden] second residual row
+    float* part_row;  // second partial-sum buffer, one row
     float2* rope_cs;  // [max_tree][d/2]
     float* attn_po;
     float* attn_pml;
@@ -117,6 +130,7 @@ int check_ctx_len(cats_ctx* c, int32_t ctx_len) {
     if (static_cast<int64_t>(ctx_len) + c->T > c->d.max_ctx) return CATS_ECAPACITY;
     c->n0 = 0;
     c->rows = c->T;
+    c->row.pend = nullptr;
     return CATS_OK;
 }
 
@@ -133,9 +147,61 @@ int seg_pad_of(const cats_ctx* c, int seg_rows) {
     return c->d.packed_weights ? (seg_rows + PACK_ROWS - 1) / PACK_ROWS * PACK_ROWS : seg_rows;
 }
 
+// The single-row product (rows == 1); g carries the mode and its operands.  It writes into the
+// partial-sum buffer that its own input does not come from.
+GemmPlan enqueue_gemv(cats_ctx* c, GemvArgs& g, const void* w0, const void* w1, const void* w2, int n_seg,
+                      int seg_rows, int K, hipStream_t st) {
+    g.w[0] = static_cast<const bf16_t*>(w0);
+    g.w[1] = static_cast<const bf16_t*>(w1 ? w1 : w0);
+    g.w[2] = static_cast<const bf16_t*>(w2 ? w2 : w0);
+    g.n_seg = n_seg;
+    g.seg_rows = seg_rows;
+    g.seg_pad = seg_pad_of(c, seg_rows);
+    g.packed = c->d.packed_weights;
+    g.N = n_seg * g.seg_pad;
+    g.K = K;
+    g.plan = make_gemm_plan(g.N, K, target_wgs(c), gemm_bn(1), gemm_kc(1));
+    g.part = (g.mode != GEMV_PLAIN && g.pend == c->part) ? c->part_row : c->part;
+    const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
+    if (timed) {
+        launch_gemv(g, st, c->prof_ev[2 * c->prof_n], c->prof_ev[2 * c->prof_n + 1]);
+        ++c->prof_n;
+    } else {
+        launch_gemv(g, st);
+    }
+    return g.plan;
+}
+GemvArgs gemv_plain(const bf16_t* x_hi, const bf16_t* x_lo) {
+    GemvArgs g{};
+    g.mode = GEMV_PLAIN;
+    g.x_hi = x_hi;
+    g.x_lo = x_lo;
+    return g;
+}
+// The pending residual update, the norm input for `gain`, and the row's sums of squares; the
+// updated row goes to x_out (null: to the residual row that is not the current one).
+GemvArgs gemv_norm(cats_ctx* c, const void* gain, float* x_out) {
+    GemvArgs g{};
+    g.mode = GEMV_NORM;
+    g.x_in = c->row.x;
+    g.x_out = x_out ? x_out : (c->row.x == c->x_row ? c->x : c->x_row);
+    g.gain = static_cast<const bf16_t*>(gain);
+    g.ss_out = c->ss;
+    g.pend = c->row.pend;
+    g.pend_plan = c->row.pend_plan;
+    g.pend_ld = c->d.hidden;
+    c->row.x = g.x_out;
+    c->row.pend = nullptr;
+    return g;
+}
+
 // One weight-streaming product over n_seg row segments of seg_rows rows each.
 GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const void* w0, const void* w1,
                       const void* w2, int n_seg, int seg_rows, int K, hipStream_t st) {
+    if (c->rows == 1) {
+        GemvArgs gv = gemv_plain(x, x_lo);
+        return enqueue_gemv(c, gv, w0, w1, w2, n_seg, seg_rows, K, st);
+    }
     GemmArgs g;
     g.x = x;
     g.x_lo = x_lo;
@@ -255,6 +321,75 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     launch_residual_norm(rn, st);
 }
 
+// The same layer for a single-row call, from and to the (x, pend) form described at cats_ctx::row.
+// On entry either a residual update is pending, or c->xn holds the row times this layer's g_attn
+// (a row kernel has just written it).  first_x_out: where the first residual update of the layer
+// leaves the row (null: the spare residual row).
+void enqueue_layer_row(cats_ctx* c, const cats_layer_weights* w, const cats_kv_layer* kv, int ctx_len,
+                       float* first_x_out, hipStream_t st) {
+    const int H = c->d.hidden, F = c->d.ffn;
+    GemvArgs g = c->row.pend ? gemv_norm(c, w->g_attn, first_x_out) : gemv_plain(c->xn, c->xn_lo);
+    GemmPlan plan = enqueue_gemv(c, g, w->wq, w->wk, w->wv, 3, H, H, st);
+    QkvRopeArgs qa;
+    qa.part = g.part;
+    qa.plan = plan;
+    qa.ns = norm_scale(c);
+    qa.cs = c->rope_cs + static_cast<size_t>(c->n0) * (c->d.head_dim / 2);
+    qa.q = c->q;
+    qa.q_lo = c->q_lo;
+    qa.kc = static_cast<bf16_t*>(kv->k);
+    qa.vt = static_cast<bf16_t*>(kv->v);
+    qa.T = 1;
+    qa.H = H;
+    qa.nh = c->d.n_heads;
+    qa.d = c->d.head_dim;
+    qa.max_ctx = c->d.max_ctx;
+    qa.row0 = ctx_len + c->n0;
+    qa.k_lo = c->k_lo;
+    qa.vt_lo = c->vt_lo;
+    qa.win0 = ctx_len % ATTN_KB + c->n0;
+    launch_qkv_rope(qa, st);
+    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
+    g = gemv_plain(c->attn, c->attn_lo);
+    c->row.pend_plan = enqueue_gemv(c, g, w->wo, nullptr, nullptr, 1, H, H, st);
+    c->row.pend = g.part;
+    if (!has_ffn(w)) return;   // attention-only block
+    g = gemv_norm(c, w->g_ffn, nullptr);
+    plan = enqueue_gemv(c, g, w->w_gate, w->w_up, nullptr, 2, F, H, st);
+    GemvArgs gd{};
+    gd.mode = GEMV_SWIGLU;
+    gd.pend = g.part;
+    gd.pend_plan = plan;
+    gd.pend_ld = 2 * seg_pad_of(c, F);
+    gd.f_pad = seg_pad_of(c, F);
+    gd.ns = norm_scale(c);
+    c->row.pend_plan = enqueue_gemv(c, gd, w->w_down, nullptr, nullptr, 1, H, F, st);
+    c->row.pend = gd.part;
+}
+
+// Brings a single-row call's row into dst (pending update added), with the next norm's input if a
+// gain is given.
+void finish_row(cats_ctx* c, float* dst, const void* gain, hipStream_t st) {
+    if (!c->row.pend && c->row.x == dst && !gain) return;
+    ResidualNormArgs rn;
+    rn.x = dst;
+    rn.x_in = c->row.x == dst ? nullptr : c->row.x;
+    rn.embed = nullptr;
+    rn.token = nullptr;
+    rn.part = c->row.pend;
+    rn.plan = c->row.pend ? c->row.pend_plan : GemmPlan{1, GEMM_KC, 1, 1, 1};
+    rn.gain = static_cast<const bf16_t*>(gain);
+    rn.xn = c->xn;
+    rn.xn_lo = c->xn_lo;
+    rn.ss = c->ss;
+    rn.T = 1;
+    rn.H = c->d.hidden;
+    rn.eps = c->d.rms_eps;
+    launch_residual_norm(rn, st);
+    c->row.x = dst;
+    c->row.pend = nullptr;
+}
+
 void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
     RopeTableArgs r;
     r.depth = c->depth;
@@ -270,9 +405,17 @@ void enqueue_rope_table(cats_ctx* c, int ctx_len, hipStream_t st) {
 // typical criterion at its parent (needs the whole tree as rows)
 void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* argmax_out,
                      float* margin_out, hipStream_t st, bool typical = false) {
-    const GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
+    GemmPlan plan;
+    const float* part = c->part;
+    if (c->rows == 1 && c->row.pend) {   // the final norm's residual update rides in the product
+        GemvArgs g = gemv_norm(c, c->row.next_gain, nullptr);
+        plan = enqueue_gemv(c, g, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
+        part = g.part;
+    } else {
+        plan = enqueue_gemm(c, c->xn, c->xn_lo, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
+    }
     ArgmaxArgs am;
-    am.part = c->part;
+    am.part = part;
     am.plan = plan;
     am.ns = norm_scale(c);
     am.T = c->rows;
@@ -294,7 +437,7 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
         TypicalArgs ta;
         ta.token = c->token;
         ta.parent = c->parent;
-        ta.part = c->part;
+        ta.part = part;
         ta.plan = plan;
         ta.ns = am.ns;
         ta.T = c->T;
@@ -407,6 +550,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_h_lo = take(Tm * F * 2);
     const size_t o_ss = take(Tm * SS_STRIDE * 4);
     const size_t o_part = take(c->part_elems * 4);
+    const size_t o_xrow = take(H * 4), o_partrow = take(part_cols * 4);
     const size_t o_cs = take(Tm * (d.head_dim / 2) * sizeof(float2));
     const size_t o_po = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * d.head_dim * 4);
     const size_t o_pml = take(static_cast<size_t>(d.n_heads) * c->attn_max_chunks * t_pad * 2 * 4);
@@ -448,6 +592,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->hact_lo = reinterpret_cast<bf16_t*>(b + o_h_lo);
     c->ss = reinterpret_cast<float*>(b + o_ss);
     c->part = reinterpret_cast<float*>(b + o_part);
+    c->x_row = reinterpret_cast<float*>(b + o_xrow);
+    c->part_row = reinterpret_cast<float*>(b + o_partrow);
     c->rope_cs = reinterpret_cast<float2*>(b + o_cs);
     c->attn_po = reinterpret_cast<float*>(b + o_po);
     c->attn_pml = reinterpret_cast<float*>(b + o_pml);
@@ -532,7 +678,13 @@ int cats_verify_layer(cats_ctx* ctx, const cats_layer_weights* w, float* hidden,
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
     launch_residual_norm(rn, st);
-    enqueue_layer(ctx, w, hidden, kv, ctx_len, nullptr, st);
+    if (ctx->rows == 1) {
+        ctx->row.x = hidden;
+        enqueue_layer_row(ctx, w, kv, ctx_len, nullptr, st);
+        finish_row(ctx, hidden, nullptr, st);
+    } else {
+        enqueue_layer(ctx, w, hidden, kv, ctx_len, nullptr, st);
+    }
     HIP_TRY(hipGetLastError());
     return CATS_OK;
 }
@@ -569,6 +721,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, int32_t n_rows, cons
     if (n_rows < 1 || n_rows > ctx->d.max_tree) return CATS_EINVAL;
     ctx->n0 = 0;
     ctx->rows = n_rows;
+    ctx->row.pend = nullptr;
     hipStream_t st = as_stream(stream);
     ResidualNormArgs rn;
     rn.x = const_cast<float*>(hidden);  // read only: no source/partials given, so nothing is written back
@@ -612,6 +765,18 @@ static void enqueue_rows_and_layers(cats_ctx* ctx, const cats_layer_weights* lay
     rn.H = ctx->d.hidden;
     rn.eps = ctx->d.rms_eps;
     launch_residual_norm(rn, st);
+    if (ctx->rows == 1) {
+        // single row: the last layer's residual update stays pending for the LM head's product
+        // (which also leaves the final row in ctx->row.x), or is carried out here if none follows
+        ctx->row.x = ctx->x;
+        ctx->row.pend = nullptr;
+        for (int l = layer_begin; l < layer_end; ++l) enqueue_layer_row(ctx, &layers[l], &kv[l], ctx_len, nullptr, st);
+        if (last_gain)
+            ctx->row.next_gain = last_gain;
+        else
+            finish_row(ctx, ctx->x, nullptr, st);
+        return;
+    }
     for (int l = layer_begin; l < layer_end; ++l) {
         const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : last_gain;
         enqueue_layer(ctx, &layers[l], ctx->x, &kv[l], ctx_len, next_gain, st);
@@ -642,11 +807,13 @@ int cats_verify_tree(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
     hipStream_t st = as_stream(stream);
     const int T = ctx->T, H = ctx->d.hidden;
     enqueue_rows_and_layers(ctx, layers, layer_begin, layer_end, embed, hidden_in, g_final, kv, ctx_len, st);
-    if (hidden_out)
+    if (hidden_out && T > 1)
         HIP_TRY(hipMemcpyAsync(hidden_out, ctx->x, sizeof(float) * T * H, hipMemcpyDeviceToDevice, st));
     int32_t* amax = argmax_out ? argmax_out : ctx->amax;
     const bool typical = ctx->accept_mode == 1;
     enqueue_lm_head(ctx, w_lm, logits_out, amax, margin_out, st, typical);
+    if (hidden_out && T == 1)   // a single row is final only once the LM head's product has updated it
+        HIP_TRY(hipMemcpyAsync(hidden_out, ctx->row.x, sizeof(float) * H, hipMemcpyDeviceToDevice, st));
     HIP_TRY(hipGetLastError());
     return enqueue_accept_compact(ctx, amax, kv, layer_begin, layer_end, ctx_len, out_dev, out_host, st,
                                   typical);
@@ -756,14 +923,18 @@ int cats_draft_chain(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
         rn.H = ctx->d.hidden;
         rn.eps = ctx->d.rms_eps;
         launch_residual_norm(rn, st);
-        for (int l = layer_begin; l < layer_end; ++l) {
-            const void* next_gain = (l + 1 < layer_end) ? layers[l + 1].g_attn : adapter->g_attn;
-            enqueue_layer(ctx, &layers[l], ctx->x, &kv[l], ctx_len, next_gain, st);
+        ctx->row.x = ctx->x;
+        ctx->row.pend = nullptr;
+        for (int l = layer_begin; l < layer_end; ++l) enqueue_layer_row(ctx, &layers[l], &kv[l], ctx_len, nullptr, st);
+        // the row after the draft layers is written straight into hidden_out: by the adapter's first
+        // product, which carries out the last layer's residual update, or by a row kernel at the end
+        float* h_k = hidden_out ? hidden_out + k * H : nullptr;
+        if (k == gamma) {
+            finish_row(ctx, h_k, nullptr, st);
+            break;
         }
-        if (hidden_out)
-            HIP_TRY(hipMemcpyAsync(hidden_out + k * H, ctx->x, sizeof(float) * H, hipMemcpyDeviceToDevice, st));
-        if (k == gamma) break;
-        enqueue_layer(ctx, adapter, ctx->x, kv_adapter, ctx_len, g_adapter_out, st);
+        enqueue_layer_row(ctx, adapter, kv_adapter, ctx_len, h_k, st);
+        ctx->row.next_gain = g_adapter_out;
         enqueue_lm_head(ctx, w_lm, nullptr, ctx->token + k + 1, nullptr, st);
     }
     HIP_TRY(hipMemcpyAsync(tokens_out, ctx->token, sizeof(int32_t) * n, hipMemcpyDeviceToDevice, st));

@@ -114,6 +114,42 @@ __device__ __forceinline__ void sum_pieces4_multi(const float* const (&p)[G], si
     }
 }
 
+// The same sums with a hook that runs between the requests of the first batch and their first use:
+// loads that the caller issues there queue behind this batch and do not hold up its arrival.
+template <int G, int B, class Hook>
+__device__ __forceinline__ void sum_pieces4_multi_hook(const float* const (&p)[G], size_t stride, const int (&pieces)[G],
+                                                       f32x4 (&acc)[G], Hook hook) {
+    int most = 0;
+    f32x4 v[G][B];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+        most = max(most, pieces[g]);
+#pragma unroll
+        for (int i = 0; i < B; ++i)
+            v[g][i] = *reinterpret_cast<const f32x4*>(p[g] + static_cast<size_t>(min(i, pieces[g] - 1)) * stride);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    hook();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < B; ++i)
+            if (i < pieces[g]) acc[g] += v[g][i];
+    for (int s0 = B; s0 < most; s0 += B) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < B; ++i)
+                v[g][i] = *reinterpret_cast<const f32x4*>(p[g] + static_cast<size_t>(min(s0 + i, pieces[g] - 1)) * stride);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < B; ++i)
+                if (s0 + i < pieces[g]) acc[g] += v[g][i];
+    }
+}
+
 // Sum of `pieces` 16-byte groups p[s * stride] (fixed order), B loads in flight.
 template <int B = 8>
 __device__ __forceinline__ f32x4 sum_pieces4(const float* p, size_t stride, int pieces) {
@@ -168,6 +204,48 @@ __device__ __forceinline__ float row_scale(const NormScale& ns, const RowSquares
     return 1.0f / sqrtf(tot / static_cast<float>(ns.H) + ns.eps);
 }
 __device__ __forceinline__ float row_scale(const NormScale& ns, int t) { return row_scale(ns, row_squares_load(ns, t)); }
+
+__device__ __forceinline__ float wave_sum64(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// The arithmetic of the row kernels, shared with the single-row product that applies the same
+// steps to its own input columns (cats_gemv_row): both must give the same bits, so the
+// multiply-add contraction is switched off here instead of being left to each call site.
+__device__ __forceinline__ float sum_squares4(f32x4 v) {
+#pragma clang fp contract(off)
+    return ((v[0] * v[0] + v[1] * v[1]) + v[2] * v[2]) + v[3] * v[3];
+}
+// (val * gain) as high and low bf16 parts; gbits: four bf16 gains
+__device__ __forceinline__ void gain_split4(f32x4 val, uint2 gbits, uint2& hi, uint2& lo) {
+#pragma clang fp contract(off)
+    const float p0 = val[0] * __uint_as_float(gbits.x << 16), p1 = val[1] * __uint_as_float(gbits.x & 0xFFFF0000u);
+    const float p2 = val[2] * __uint_as_float(gbits.y << 16), p3 = val[3] * __uint_as_float(gbits.y & 0xFFFF0000u);
+    split_bf2(p0, p1, hi.x, lo.x);
+    split_bf2(p2, p3, hi.y, lo.y);
+}
+// silu(gate * rs) * (up * rs) as high and low bf16 parts
+__device__ __forceinline__ void swiglu_split4(f32x4 gt, f32x4 up, float rs, uint2& hi, uint2& lo) {
+#pragma clang fp contract(off)
+    float hv[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float g = gt[e] * rs, u = up[e] * rs;
+        hv[e] = g / (1.0f + __expf(-g)) * u;
+    }
+    split_bf2(hv[0], hv[1], hi.x, lo.x);
+    split_bf2(hv[2], hv[3], hi.y, lo.y);
+}
+// four values from their high and low bf16 parts
+__device__ __forceinline__ f32x4 join_bf4(uint2 hi, uint2 lo) {
+#pragma clang fp contract(off)
+    return f32x4{__uint_as_float(hi.x << 16) + __uint_as_float(lo.x << 16),
+                 __uint_as_float(hi.x & 0xFFFF0000u) + __uint_as_float(lo.x & 0xFFFF0000u),
+                 __uint_as_float(hi.y << 16) + __uint_as_float(lo.y << 16),
+                 __uint_as_float(hi.y & 0xFFFF0000u) + __uint_as_float(lo.y & 0xFFFF0000u)};
+}
 
 struct ResidualNormArgs {
     float* x;               // [T][H] residual stream, in/out
@@ -245,6 +323,39 @@ struct ArgmaxArgs {
 };
 constexpr int ARGMAX_SLICES = 16;
 void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
+
+// ---------------------------------------------------------------- single-row product
+// The same product for a single row (T = 1: the stage-1 draft loop and plain decoding), with the
+// row kernel that would run in front of it folded into the way each workgroup builds the input
+// columns of its own work items.  Same plan (128-row tiles, 256-wide items), weight layouts and
+// partial-tile layout ([piece][N]) as the GEMM above, so the consumers are the same kernels.
+//   GEMV_PLAIN   X = x_hi + x_lo (a row that a row kernel or the attention kernel has written)
+//   GEMV_NORM    x_out = x_in + sum of the pieces of the product before (residual update);
+//                X = x_out * gain (as high + low bf16 parts, like the row kernel); the workgroup that
+//                owns item (tile 0, chunk c) also writes x_out and ss_out[c] for chunk c's columns
+//   GEMV_SWIGLU  X = silu(g) * u, g | u = norm factor * sums of the pieces of the gate|up product
+// x_in and x_out must not overlap; pend must not be the buffer `part` points into.
+enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_SWIGLU = 2 };
+struct GemvArgs {
+    const bf16_t* w[3];
+    int n_seg, seg_rows, seg_pad;
+    int packed;
+    int N, K;
+    GemmPlan plan;       // bn 128, kc 256
+    float* part;         // [pieces][N]
+    int mode;
+    const bf16_t *x_hi, *x_lo;   // PLAIN: [K]
+    const float* x_in;           // NORM: [K]
+    float* x_out;                // NORM: [K] or null
+    const bf16_t* gain;          // NORM: [K]
+    float* ss_out;               // NORM: [SS_STRIDE]
+    const float* pend;           // NORM, SWIGLU: [pieces][pend_ld] partial sums of the product before
+    GemmPlan pend_plan;
+    int pend_ld;
+    NormScale ns;                // SWIGLU: the norm factor of the row (row 0 of ns.ss)
+    int f_pad;                   // SWIGLU: column offset of the up half
+};
+void launch_gemv(const GemvArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---------------------------------------------------------------- attention
 // The cache holds bf16 rows.  The rows that the running call itself appends (the tree nodes it

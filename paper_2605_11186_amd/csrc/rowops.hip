@@ -7,12 +7,6 @@
 
 namespace {
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
-}
-
 // x[t] <- (x_in[t] | embed[token[t]] | x[t]) + sum of the GEMM pieces;  xn[t] = x[t] * gain as
 // high + low bf16 parts;  ss[t][block] = sum of x^2 over the block's columns.  One wave per
 // (row, block of 256 columns): nothing here needs a whole row, so the launch has T * H/256
@@ -34,21 +28,17 @@ __global__ __launch_bounds__(64) void cats_residual_rmsnorm(ResidualNormArgs a) 
         if (a.part) {
             val += sum_pieces4<16>(a.part + row + j, static_cast<size_t>(a.T) * a.H, plan_pieces(a.plan, j / a.plan.bn));
         }
-        ss = val[0] * val[0] + val[1] * val[1] + val[2] * val[2] + val[3] * val[3];
+        ss = sum_squares4(val);
         if (a.embed || a.x_in || a.part) *reinterpret_cast<f32x4*>(a.x + row + j) = val;
         if (a.gain) {
-            const uint2 gbits = *reinterpret_cast<const uint2*>(a.gain + j);
             uint2 hi, lo;
-            split_bf2(val[0] * __uint_as_float(gbits.x << 16), val[1] * __uint_as_float(gbits.x & 0xFFFF0000u),
-                      hi.x, lo.x);
-            split_bf2(val[2] * __uint_as_float(gbits.y << 16), val[3] * __uint_as_float(gbits.y & 0xFFFF0000u),
-                      hi.y, lo.y);
+            gain_split4(val, *reinterpret_cast<const uint2*>(a.gain + j), hi, lo);
             *reinterpret_cast<uint2*>(a.xn + row + j) = hi;
             *reinterpret_cast<uint2*>(a.xn_lo + row + j) = lo;
         }
     }
     if (!a.gain) return;
-    ss = wave_sum(ss);
+    ss = wave_sum64(ss);
     if (threadIdx.x == 0) a.ss[t * SS_STRIDE + blk] = ss;
 }
 
@@ -186,16 +176,8 @@ __global__ void cats_swiglu(SwigluArgs a) {
     const int np[2] = {plan_pieces(a.plan, n / a.plan.bn), plan_pieces(a.plan, (a.f_pad + n) / a.plan.bn)};
     f32x4 gu[2];
     sum_pieces4_multi<2, 4>(pp, stride, np, gu);
-    f32x4 gt = gu[0], up = gu[1];
-    const float rs = row_scale(a.ns, sq);
-    gt *= rs;
-    up *= rs;
-    float hv[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) hv[e] = gt[e] / (1.0f + __expf(-gt[e])) * up[e];
     uint2 hi, lo;
-    split_bf2(hv[0], hv[1], hi.x, lo.x);
-    split_bf2(hv[2], hv[3], hi.y, lo.y);
+    swiglu_split4(gu[0], gu[1], row_scale(a.ns, sq), hi, lo);
     const size_t o = static_cast<size_t>(t) * a.F + n;
     *reinterpret_cast<uint2*>(a.h + o) = hi;
     *reinterpret_cast<uint2*>(a.h_lo + o) = lo;

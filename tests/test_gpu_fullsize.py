@@ -237,6 +237,19 @@ def test_7b_layer_shape_cascaded_cycle():
         pair.close()
 
 
+def test_single_row_with_more_work_items_than_one_staging_round():
+    """One token through one layer and an LM head of 140000 x 2048: every workgroup of the single-row
+    product then owns 34 to 36 work items, more than the 32 whose input columns it holds in LDS at a
+    time (a second staging round), and more than the 16 one staging pass covers."""
+    dims = synth.ModelDims(1, 2048, 16, 128, 5632, 140000)
+    pair = Pair(dims, 17, max_ctx=384, max_tree=8, precision="f32", n_layers=1, packed=True)
+    try:
+        parent, depth = synth.chain_tree(1)
+        compare_with_oracle(pair, 300, np.array([4242], dtype=np.int32), parent, depth, 23)
+    finally:
+        pair.close()
+
+
 def test_largest_supported_layer_shape_and_deepest_tree():
     """The limits of the library in one case: hidden 8192 (the widest the norm scratch allows), 64
     heads of 128, a 128-node tree (CATS_MAX_TREE) that reaches depth 16 (CATS_MAX_DEPTH), one

@@ -126,6 +126,18 @@ def test_odd_chunk_counts_every_accumulator_depth(odd, T):
     check_step(odd, kc, vc, ks, vs, S, tok, parent, depth)
 
 
+@pytest.mark.parametrize("S", [0, 37, 191])
+def test_single_row_on_ragged_shapes(odd, S):
+    """A one-node tree (plain decoding of one token) runs on the single-row product, which builds
+    its own input columns from the partial sums of the product before it: hidden 384 and FFN 1104
+    end inside a 256-wide item, the vocabulary inside a tile; both weight layouts."""
+    parent, depth = synth.chain_tree(1)
+    tok = np.array([S % ODD.vocab], dtype=np.int32)
+    kc, vc = odd.oracle_cache_random(SEED + 100 + S, S)
+    ks, vs = odd.device_cache_from_oracle(kc, vc, S)
+    check_step(odd, kc, vc, ks, vs, S, tok, parent, depth)
+
+
 @pytest.mark.parametrize("S", [0, 1, 31, 32, 33, 100, 191])
 def test_verify_tree_ragged_context_lengths(tiny, S):
     parent, depth = synth.random_tree(45, 6, S + 1)

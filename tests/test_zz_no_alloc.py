@@ -4,6 +4,7 @@ scratch differs: a fixed array in the library instead of the context's allocatio
 row, the second with a smaller input, so that whatever the first call left in the shared scratch
 must not leak into the second."""
 import ctypes
+import gc
 
 import numpy as np
 import pytest
@@ -29,6 +30,7 @@ def _case(dims, ctx, max_ctx, S, T, seed):
     cats.cats_set_tree(ctx, tok, parent, depth)
     cats.cats_tree_attention(ctx, q, kv, S, ref)
     out = torch.full((T, dims.hidden), float("nan"), dtype=torch.bfloat16, device="cuda")
+    gc.collect()   # tensors of earlier tests that are still waiting for the collector must not be freed in between
     before = torch.cuda.memory_allocated()
     cats.cats_tree_attention_noalloc(q, kv, parent, dims.n_heads, dims.head_dim, max_ctx, S, out)
     assert torch.cuda.memory_allocated() == before
