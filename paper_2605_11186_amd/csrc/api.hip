@@ -259,6 +259,37 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
     launch_attention(a, st);
 }
 
+// The attention block of a single-row call: q|k|v from the product's partial sums, cache append
+// and attention over the context and the node's own path in one kernel.  Key chunks of at least
+// four 32-key blocks, as many as the context's scratch holds at most.
+void enqueue_row_attention(cats_ctx* c, const float* part, const GemmPlan& plan, const cats_kv_layer* kv,
+                           int ctx_len, hipStream_t st) {
+    DecodeAttnArgs a;
+    a.part = part;
+    a.plan = plan;
+    a.ns = norm_scale(c);
+    a.cs = c->rope_cs + static_cast<size_t>(c->n0) * (c->d.head_dim / 2);
+    a.kc = static_cast<bf16_t*>(kv->k);
+    a.vt = static_cast<bf16_t*>(kv->v);
+    a.anc = c->anc;
+    a.node = c->n0;
+    a.H = c->d.hidden;
+    a.nh = c->d.n_heads;
+    a.d = c->d.head_dim;
+    a.max_ctx = c->d.max_ctx;
+    a.ctx_len = ctx_len;
+    const int n_blocks = (ctx_len + c->n0 + 1 + ATTN_KB - 1) / ATTN_KB;
+    const int per_chunk = std::max(DEC_TILE / ATTN_KB, (n_blocks + DEC_MAX_CHUNKS - 1) / DEC_MAX_CHUNKS);
+    a.n_chunks = (n_blocks + per_chunk - 1) / per_chunk;
+    a.span = per_chunk * ATTN_KB;
+    a.po = c->attn_po;
+    a.pml = c->attn_pml;
+    a.arrivals = c->attn_arrivals;
+    a.out = c->attn;
+    a.out_lo = c->attn_lo;
+    launch_decode_attention(a, st);
+}
+
 // One decoder layer.  On entry c->xn holds rmsnorm(x)*g_attn of this layer; on
 // exit x is updated and, if next_gain is given, c->xn holds rmsnorm(x)*next_gain.
 void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cats_kv_layer* kv,
@@ -266,6 +297,7 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     const int H = c->d.hidden, F = c->d.ffn, T = c->rows;   // nodes n0 .. n0 + rows - 1
     // attention block
     GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, 3, H, H, st);
+    if (T == 1) enqueue_row_attention(c, c->part, plan, kv, ctx_len, st);
     QkvRopeArgs qa;
     qa.part = c->part;
     qa.plan = plan;
@@ -284,8 +316,10 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     qa.k_lo = c->k_lo;
     qa.vt_lo = c->vt_lo;
     qa.win0 = ctx_len % ATTN_KB + c->n0;
-    launch_qkv_rope(qa, st);
-    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
+    if (T > 1) {
+        launch_qkv_rope(qa, st);
+        enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
+    }
     plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
@@ -330,26 +364,7 @@ void enqueue_layer_row(cats_ctx* c, const cats_layer_weights* w, const cats_kv_l
     const int H = c->d.hidden, F = c->d.ffn;
     GemvArgs g = c->row.pend ? gemv_norm(c, w->g_attn, first_x_out) : gemv_plain(c->xn, c->xn_lo);
     GemmPlan plan = enqueue_gemv(c, g, w->wq, w->wk, w->wv, 3, H, H, st);
-    QkvRopeArgs qa;
-    qa.part = g.part;
-    qa.plan = plan;
-    qa.ns = norm_scale(c);
-    qa.cs = c->rope_cs + static_cast<size_t>(c->n0) * (c->d.head_dim / 2);
-    qa.q = c->q;
-    qa.q_lo = c->q_lo;
-    qa.kc = static_cast<bf16_t*>(kv->k);
-    qa.vt = static_cast<bf16_t*>(kv->v);
-    qa.T = 1;
-    qa.H = H;
-    qa.nh = c->d.n_heads;
-    qa.d = c->d.head_dim;
-    qa.max_ctx = c->d.max_ctx;
-    qa.row0 = ctx_len + c->n0;
-    qa.k_lo = c->k_lo;
-    qa.vt_lo = c->vt_lo;
-    qa.win0 = ctx_len % ATTN_KB + c->n0;
-    launch_qkv_rope(qa, st);
-    enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
+    enqueue_row_attention(c, g.part, plan, kv, ctx_len, st);
     g = gemv_plain(c->attn, c->attn_lo);
     c->row.pend_plan = enqueue_gemv(c, g, w->wo, nullptr, nullptr, 1, H, H, st);
     c->row.pend = g.part;

@@ -446,6 +446,257 @@ __global__ __launch_bounds__(64 * W) void cats_tree_attention_kernel(AttnArgs a)
     if (threadIdx.x == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
+// ---------------------------------------------------------------- single query
+// One query node against rows [0, ctx_len) and its own path (see DecodeAttnArgs).  grid (chunks,
+// heads), 256 threads; a workgroup takes its chunk in passes of DEC_TILE keys (normally one).
+// Nothing here is a matrix product worth a matrix core: a pass is 64 KB of keys and values, and
+// the launch is one memory round trip (partial sums, keys and values are all requested before the
+// first of them is used), a few hundred fused multiply-adds per thread, and the hand-over of the
+// chunk results to the last workgroup of the head.
+//   scores: a key row is D/8 16-byte pieces, one per lane, summed over those lanes;
+//   values: the cache is transposed, a dim's 128 keys are 16 16-byte pieces, one per lane.
+// Rows that must stay invisible (later siblings, rows past the tree, the node's own row, which is
+// being written meanwhile) are excluded by selects, never by a multiplication with zero.
+__device__ __forceinline__ bool mask_bit(const u32x4& m, int i) {
+    const uint32_t w = i < 64 ? (i < 32 ? m[0] : m[1]) : (i < 96 ? m[2] : m[3]);
+    return (w >> (i & 31)) & 1u;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void cats_decode_attention(DecodeAttnArgs a) {
+    constexpr int LPK = D / 8;           // lanes per key row
+    constexpr int KPP = 256 / LPK;       // keys per score pass
+    constexpr int KP = DEC_TILE / KPP;   // score passes per tile
+    constexpr int VP = D / 16;           // value passes per tile (16 dims each)
+    constexpr int HALF = D / 2;
+    constexpr int PB = 8;                // partial sums requested at once per column
+    __shared__ float s_q[D], s_kn[D], s_vn[D];
+    __shared__ float s_sc[DEC_TILE];
+    __shared__ __align__(16) float s_o[D];
+    __shared__ float s_new;
+    __shared__ int s_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = blockIdx.x, h = blockIdx.y;
+    const int S = a.ctx_len, node = a.node;
+    const int n_keys = S + node + 1, own = S + node;
+    const int key_begin = chunk * a.span, key_end = min(key_begin + a.span, n_keys);
+    const bool owner = own >= key_begin && own < key_end;
+    const u32x4 anc = a.anc[node];
+    bf16_t* kbase = a.kc + static_cast<size_t>(h) * a.max_ctx * D;
+    bf16_t* vbase = a.vt + static_cast<size_t>(h) * D * a.max_ctx;
+    const float scale = rsqrtf(static_cast<float>(D)) * 1.44269504088896340736f;   // 1/sqrt(d) * log2(e)
+    auto visible = [&](int j) { return j < key_end && j != own && (j < S || mask_bit(anc, j - S)); };
+
+    // requests: this wave's two columns of q, k or v (waves 0..2; k and v only where the node's
+    // own row lives), then the first tile's keys and values
+    const int role = wave;
+    const bool builds = lane < HALF && (role == 0 || (owner && role <= 2));
+    const int N = 3 * a.H;
+    const int col = min(role, 2) * a.H + h * D + min(lane, HALF - 1);
+    const int pieces = plan_pieces(a.plan, col / a.plan.bn);   // both columns lie in the same tile
+    float pa[PB], pb[PB];
+    RowSquares sq;
+    float2 cs = make_float2(1.f, 0.f);
+    if (builds) {
+        sq = row_squares_load(a.ns, 0);
+        if (role < 2) cs = a.cs[lane];
+#pragma unroll
+        for (int i = 0; i < PB; ++i) {
+            const float* p = a.part + static_cast<size_t>(min(i, pieces - 1)) * N + col;
+            pa[i] = p[0];
+            pb[i] = p[HALF];
+        }
+    }
+    u32x4 kf[KP], vf[VP];
+    auto load_tile = [&](int t0) {
+#pragma unroll
+        for (int p = 0; p < KP; ++p) {
+            const int key = min(t0 + KPP * p + tid / LPK, a.max_ctx - 1);
+            kf[p] = *reinterpret_cast<const u32x4*>(kbase + static_cast<size_t>(key) * D + 8 * (tid % LPK));
+        }
+#pragma unroll
+        for (int p = 0; p < VP; ++p) {
+            const int j0 = min(t0 + 8 * (tid % 16), a.max_ctx - 8);
+            vf[p] = *reinterpret_cast<const u32x4*>(vbase + static_cast<size_t>(16 * p + tid / 16) * a.max_ctx + j0);
+        }
+    };
+    load_tile(key_begin);
+
+    // q (every workgroup), k and v of the node's own row (its owner): sum, scale, rotate
+    if (builds) {
+        float va = 0.f, vb = 0.f;
+#pragma unroll
+        for (int i = 0; i < PB; ++i)
+            if (i < pieces) {
+                va += pa[i];
+                vb += pb[i];
+            }
+        for (int i = PB; i < pieces; ++i) {
+            const float* p = a.part + static_cast<size_t>(i) * N + col;
+            va += p[0];
+            vb += p[HALF];
+        }
+        const float rs = row_scale(a.ns, sq);
+        va *= rs;
+        vb *= rs;
+        const float r0 = role < 2 ? va * cs.x - vb * cs.y : va;
+        const float r1 = role < 2 ? va * cs.y + vb * cs.x : vb;
+        if (role == 0) {
+            s_q[lane] = r0;
+            s_q[lane + HALF] = r1;
+        } else {
+            const bf16_t h0 = f2bf(r0), h1 = f2bf(r1);
+            float* dst = role == 1 ? s_kn : s_vn;
+            dst[lane] = bf2f(h0) + bf2f(f2bf(r0 - bf2f(h0)));   // the row as later products of this call see it:
+            dst[lane + HALF] = bf2f(h1) + bf2f(f2bf(r1 - bf2f(h1)));   // high + low part
+            if (role == 1) {
+                kbase[static_cast<size_t>(own) * D + lane] = h0;
+                kbase[static_cast<size_t>(own) * D + lane + HALF] = h1;
+            } else {
+                vbase[static_cast<size_t>(lane) * a.max_ctx + own] = h0;
+                vbase[static_cast<size_t>(lane + HALF) * a.max_ctx + own] = h1;
+            }
+        }
+    }
+    __syncthreads();
+    float qs[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qs[e] = s_q[8 * (tid % LPK) + e];
+    if (wave == 3 && owner) {   // the node's own key
+        float acc = 0.f;
+        for (int d = lane; d < D; d += 64) acc += s_q[d] * s_kn[d];
+        acc = wave_sum64(acc);
+        if (lane == 0) s_new = acc * scale;
+    }
+
+    float m_run = -1e30f, l_run = 0.f, o_run[VP];
+#pragma unroll
+    for (int p = 0; p < VP; ++p) o_run[p] = 0.f;
+    for (int t0 = key_begin;;) {
+        // scores of the tile's keys
+#pragma unroll
+        for (int p = 0; p < KP; ++p) {
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                dot = fmaf(__uint_as_float(kf[p][e] << 16), qs[2 * e], dot);
+                dot = fmaf(__uint_as_float(kf[p][e] & 0xFFFF0000u), qs[2 * e + 1], dot);
+            }
+#pragma unroll
+            for (int o = LPK / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o);
+            const int kl = KPP * p + tid / LPK;
+            if (tid % LPK == 0) s_sc[kl] = visible(t0 + kl) ? dot * scale : -INFINITY;
+        }
+        __syncthreads();
+        const bool own_here = owner && own >= t0 && own < t0 + DEC_TILE;
+        // tile maximum (every wave works it out for itself), this thread's 8 keys' weights, tile sum
+        float m_t = fmaxf(s_sc[lane], s_sc[lane + 64]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m_t = fmaxf(m_t, __shfl_xor(m_t, o));
+        if (own_here) m_t = fmaxf(m_t, s_new);
+        m_t = fmaxf(m_t, -1e30f);
+        float pw[8], l_t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            pw[e] = __builtin_amdgcn_exp2f(s_sc[8 * (tid % 16) + e] - m_t);
+            l_t += pw[e];
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) l_t += __shfl_xor(l_t, o);
+        const float p_new = own_here ? __builtin_amdgcn_exp2f(s_new - m_t) : 0.f;
+        l_t += p_new;
+        // weighted values: 16 dims per pass, a dim's keys over 16 lanes
+        const float m_new = fmaxf(m_run, m_t);
+        const float c_run = __builtin_amdgcn_exp2f(m_run - m_new), c_t = __builtin_amdgcn_exp2f(m_t - m_new);
+#pragma unroll
+        for (int p = 0; p < VP; ++p) {
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v0 = __uint_as_float(vf[p][e] << 16), v1 = __uint_as_float(vf[p][e] & 0xFFFF0000u);
+                acc += pw[2 * e] != 0.f ? pw[2 * e] * v0 : 0.f;
+                acc += pw[2 * e + 1] != 0.f ? pw[2 * e + 1] * v1 : 0.f;
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+            if (own_here) acc += p_new * s_vn[16 * p + tid / 16];
+            o_run[p] = o_run[p] * c_run + acc * c_t;
+        }
+        l_run = l_run * c_run + l_t * c_t;
+        m_run = m_new;
+        t0 += DEC_TILE;
+        if (t0 >= key_end) break;
+        __syncthreads();   // the scores are overwritten by the next tile
+        load_tile(t0);
+    }
+    if (tid % 16 == 0) {
+#pragma unroll
+        for (int p = 0; p < VP; ++p) s_o[16 * p + tid / 16] = o_run[p];
+    }
+    __syncthreads();
+
+    // out[h * D + dims] = num / den as high and low bf16 parts, four dims per thread
+    auto write_out = [&](f32x4 num, float den) {
+        const float inv = 1.0f / den;
+        uint2 hi, lo;
+        split_bf2(num[0] * inv, num[1] * inv, hi.x, lo.x);
+        split_bf2(num[2] * inv, num[3] * inv, hi.y, lo.y);
+        *reinterpret_cast<uint2*>(a.out + h * D + 4 * tid) = hi;
+        *reinterpret_cast<uint2*>(a.out_lo + h * D + 4 * tid) = lo;
+    };
+    if (a.n_chunks == 1) {
+        if (tid < D / 4) write_out(*reinterpret_cast<const f32x4*>(&s_o[4 * tid]), l_run);
+        return;
+    }
+    // publish the chunk (device-coherent 16-byte stores, acknowledged before the arrival count is
+    // raised); the head's last workgroup adds the chunks in index order
+    const size_t slot = static_cast<size_t>(h) * a.n_chunks + chunk;
+    if (tid < D / 4) store_coherent16(a.po + slot * D + 4 * tid, *reinterpret_cast<const f32x4*>(&s_o[4 * tid]));
+    if (tid == 0) {
+        __hip_atomic_store(a.pml + slot * 2, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.pml + slot * 2 + 1, l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0)
+        s_last = __hip_atomic_fetch_add(a.arrivals + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.n_chunks - 1;
+    __syncthreads();
+    if (!s_last || tid >= D / 4) return;
+    constexpr int MG = 8;
+    float Mg = -1e30f, den = 0.f;
+    f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < a.n_chunks; c0 += MG) {
+        f32x4 v[MG];
+        float mc[MG], lc[MG];
+#pragma unroll
+        for (int j = 0; j < MG; ++j) {
+            const size_t sl = static_cast<size_t>(h) * a.n_chunks + min(c0 + j, a.n_chunks - 1);
+            mc[j] = __hip_atomic_load(a.pml + sl * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            lc[j] = __hip_atomic_load(a.pml + sl * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v[j] = load_coherent16(a.po + sl * D + 4 * tid);
+        }
+#pragma unroll
+        for (int j = 0; j < MG; ++j) wait_coherent(v[j]);
+        float Mn = Mg;
+#pragma unroll
+        for (int j = 0; j < MG; ++j) Mn = fmaxf(Mn, mc[j]);
+        const float resc = __builtin_amdgcn_exp2f(Mg - Mn);
+        den *= resc;
+        num *= resc;
+        Mg = Mn;
+#pragma unroll
+        for (int j = 0; j < MG; ++j)
+            if (c0 + j < a.n_chunks) {
+                const float wc = __builtin_amdgcn_exp2f(mc[j] - Mg);
+                den += wc * lc[j];
+                num += wc * v[j];
+            }
+    }
+    write_out(num, den);
+    if (tid == 0) __hip_atomic_store(a.arrivals + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+}
+
 // Ancestor-or-self set of every node as a 128-bit mask (bit a of anc[i] set when a is on the
 // path root..i): the tree attention mask in compact form.  One workgroup, parent[] in LDS.
 __global__ __launch_bounds__(CATS_MAX_TREE) void cats_tree_masks(const int32_t* parent, int T, u32x4* anc) {
@@ -478,6 +729,14 @@ void launch_zero_i32(int* p, int n, hipStream_t st) {
 
 void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st) {
     hipLaunchKernelGGL(cats_tree_masks, dim3(1), dim3(CATS_MAX_TREE), 0, st, parent, T, anc);
+}
+
+void launch_decode_attention(const DecodeAttnArgs& a, hipStream_t st) {
+    const dim3 grid(a.n_chunks, a.nh);
+    if (a.d == 128)
+        hipLaunchKernelGGL((cats_decode_attention<128>), grid, dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((cats_decode_attention<64>), grid, dim3(256), 0, st, a);
 }
 
 void launch_attention(const AttnArgs& a, hipStream_t st) {

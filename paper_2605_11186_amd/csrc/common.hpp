@@ -392,6 +392,31 @@ constexpr int ATTN_KB = 32;    // keys per block
 constexpr int ATTN_WAVES = 4;
 constexpr int ATTN_QN = 32;
 constexpr int ATTN_MAX_QGROUPS = CATS_MAX_TREE / ATTN_QN;   // query groups per head at most
+// Attention of a single-row call (one query node, T = 1 per step: the stage-1 draft loop, plain
+// decoding) with the q|k|v step folded in: every workgroup adds up the query columns of its head
+// from the q|k|v product's partial sums, scales and rotates them; the workgroup whose key chunk
+// holds the node's own cache row does the same for the key and value columns, appends them to the
+// cache (bf16) and uses them (high + low part) without reading them back.
+constexpr int DEC_TILE = 128;       // keys per pass of a workgroup
+constexpr int DEC_MAX_CHUNKS = 32;  // key chunks per head at most (the context's scratch holds that many)
+struct DecodeAttnArgs {
+    const float* part;   // [pieces][3H] partial sums of q | k | v, still to be scaled by the row's norm factor
+    GemmPlan plan;
+    NormScale ns;        // row 0
+    const float2* cs;    // [d/2] (cos, sin) at the node's position
+    bf16_t* kc;          // [nh][max_ctx][d]; row ctx_len + node is written
+    bf16_t* vt;          // [nh][d][max_ctx]
+    const u32x4* anc;    // ancestor-or-self masks of the uploaded tree
+    int node;            // the query node; keys: rows [0, ctx_len) and ctx_len + j for j <= node on its path
+    int H, nh, d, max_ctx, ctx_len;
+    int n_chunks, span;  // chunk c owns keys [c * span, (c + 1) * span); span is a multiple of 32
+    float* po;           // [nh][n_chunks][d]
+    float* pml;          // [nh][n_chunks][2]
+    int* arrivals;       // [nh], zero between launches
+    bf16_t* out;         // [H] high parts of the attention output
+    bf16_t* out_lo;      // [H] low parts
+};
+void launch_decode_attention(const DecodeAttnArgs& a, hipStream_t st);
 void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st);
 void launch_attention(const AttnArgs& a, hipStream_t st);
 void launch_zero_i32(int* p, int n, hipStream_t st);   // fill kernel (a memset node must not enter a captured graph)

@@ -138,6 +138,21 @@ def test_single_row_on_ragged_shapes(odd, S):
     check_step(odd, kc, vc, ks, vs, S, tok, parent, depth)
 
 
+@pytest.mark.parametrize("head_dim,S", [(64, 4200), (128, 4200), (64, 9100), (128, 9100)])
+def test_single_row_behind_a_long_context(head_dim, S):
+    """One token behind a context of more than 32 x 128 keys: the single-query attention then takes
+    its key chunks in several passes (4200: two, the second ragged; 9100: three), for both head sizes."""
+    dims = synth.ModelDims(1, 256, 256 // head_dim, head_dim, 688, 1000)
+    p = Pair(dims, SEED + 7, max_ctx=9216, max_tree=8, packed=True)
+    try:
+        parent, depth = synth.chain_tree(1)
+        kc, vc = p.oracle_cache_random(SEED + S, S)
+        ks, vs = p.device_cache_from_oracle(kc, vc, S)
+        check_step(p, kc, vc, ks, vs, S, np.array([7], dtype=np.int32), parent, depth)
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("S", [0, 1, 31, 32, 33, 100, 191])
 def test_verify_tree_ragged_context_lengths(tiny, S):
     parent, depth = synth.random_tree(45, 6, S + 1)
