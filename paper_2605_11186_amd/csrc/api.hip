@@ -40,13 +40,16 @@ struct cats_ctx {
     // steps into the product behind them.  Between two products the row is therefore (x, pend):
     // the residual row as of its last update and the partial sums of the last product, still to be
     // added.  Products alternate between two partial-sum buffers (a product reads the one before
-    // while it writes its own) and residual updates between two rows.
+    // while it writes its own) and residual updates between two rows.  At the start of the draft
+    // loop's steps the row is (embed, token) instead: an embedding row that no kernel has copied yet.
     struct {
         float* x;               // the residual row as of its last update
+        const bf16_t* embed;    // not null: the row is embed[*token] and x does not hold it yet
+        const int32_t* token;   // device
         const float* pend;      // [pieces][hidden] partial sums still to be added to it; null: none
         GemmPlan pend_plan;
         const void* next_gain;  // gain of the norm that follows the pending update (LM head)
-    } row = {nullptr, nullptr, {}, nullptr};
+    } row = {nullptr, nullptr, nullptr, nullptr, {}, nullptr};
     float* x_row;     // [hidden] second residual row
     float* part_row;  // second partial-sum buffer, one row
     float2* rope_cs;  // [max_tree][d/2]
@@ -131,6 +134,7 @@ int check_ctx_len(cats_ctx* c, int32_t ctx_len) {
     c->n0 = 0;
     c->rows = c->T;
     c->row.pend = nullptr;
+    c->row.embed = nullptr;
     return CATS_OK;
 }
 
@@ -184,6 +188,8 @@ GemvArgs gemv_norm(cats_ctx* c, const void* gain, float* x_out) {
     GemvArgs g{};
     g.mode = GEMV_NORM;
     g.x_in = c->row.x;
+    g.embed = c->row.embed;
+    g.token = c->row.token;
     g.x_out = x_out ? x_out : (c->row.x == c->x_row ? c->x : c->x_row);
     g.gain = static_cast<const bf16_t*>(gain);
     g.ss_out = c->ss;
@@ -191,7 +197,18 @@ GemvArgs gemv_norm(cats_ctx* c, const void* gain, float* x_out) {
     g.pend_plan = c->row.pend_plan;
     g.pend_ld = c->d.hidden;
     c->row.x = g.x_out;
+    c->row.embed = nullptr;
     c->row.pend = nullptr;
+    return g;
+}
+// The attention output as cats_decode_attention left it: one partial result per key chunk.
+GemvArgs gemv_attn(const cats_ctx* c, int n_chunks) {
+    GemvArgs g{};
+    g.mode = GEMV_ATTN;
+    g.po = c->attn_po;
+    g.pml = c->attn_pml;
+    g.n_chunks = n_chunks;
+    g.head_dim = c->d.head_dim;
     return g;
 }
 
@@ -261,8 +278,9 @@ void enqueue_attention(cats_ctx* c, const bf16_t* q, const bf16_t* q_lo, const c
 
 // The attention block of a single-row call: q|k|v from the product's partial sums, cache append
 // and attention over the context and the node's own path in one kernel.  Key chunks of at least
-// four 32-key blocks, as many as the context's scratch holds at most.
-void enqueue_row_attention(cats_ctx* c, const float* part, const GemmPlan& plan, const cats_kv_layer* kv,
+// four 32-key blocks, as many as the context's scratch holds at most.  Returns the number of
+// chunks: the product that follows merges their results (gemv_attn).
+int enqueue_row_attention(cats_ctx* c, const float* part, const GemmPlan& plan, const cats_kv_layer* kv,
                            int ctx_len, hipStream_t st) {
     DecodeAttnArgs a;
     a.part = part;
@@ -284,10 +302,8 @@ void enqueue_row_attention(cats_ctx* c, const float* part, const GemmPlan& plan,
     a.span = per_chunk * ATTN_KB;
     a.po = c->attn_po;
     a.pml = c->attn_pml;
-    a.arrivals = c->attn_arrivals;
-    a.out = c->attn;
-    a.out_lo = c->attn_lo;
     launch_decode_attention(a, st);
+    return a.n_chunks;
 }
 
 // One decoder layer.  On entry c->xn holds rmsnorm(x)*g_attn of this layer; on
@@ -297,7 +313,6 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     const int H = c->d.hidden, F = c->d.ffn, T = c->rows;   // nodes n0 .. n0 + rows - 1
     // attention block
     GemmPlan plan = enqueue_gemm(c, c->xn, c->xn_lo, w->wq, w->wk, w->wv, 3, H, H, st);
-    if (T == 1) enqueue_row_attention(c, c->part, plan, kv, ctx_len, st);
     QkvRopeArgs qa;
     qa.part = c->part;
     qa.plan = plan;
@@ -319,8 +334,11 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
     if (T > 1) {
         launch_qkv_rope(qa, st);
         enqueue_attention(c, c->q, c->q_lo, kv, ctx_len, c->attn, c->attn_lo, true, st);
+        plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
+    } else {
+        GemvArgs g = gemv_attn(c, enqueue_row_attention(c, c->part, plan, kv, ctx_len, st));
+        plan = enqueue_gemv(c, g, w->wo, nullptr, nullptr, 1, H, H, st);
     }
-    plan = enqueue_gemm(c, c->attn, c->attn_lo, w->wo, nullptr, nullptr, 1, H, H, st);
     ResidualNormArgs rn;
     rn.x = x;
     rn.x_in = nullptr;
@@ -356,16 +374,16 @@ void enqueue_layer(cats_ctx* c, const cats_layer_weights* w, float* x, const cat
 }
 
 // The same layer for a single-row call, from and to the (x, pend) form described at cats_ctx::row.
-// On entry either a residual update is pending, or c->xn holds the row times this layer's g_attn
-// (a row kernel has just written it).  first_x_out: where the first residual update of the layer
+// On entry either a residual update is pending or the row is still an embedding row (the first
+// product then works out its own input), or c->xn holds the row times this layer's g_attn (a row
+// kernel has just written it).  first_x_out: where the first residual update of the layer
 // leaves the row (null: the spare residual row).
 void enqueue_layer_row(cats_ctx* c, const cats_layer_weights* w, const cats_kv_layer* kv, int ctx_len,
                        float* first_x_out, hipStream_t st) {
     const int H = c->d.hidden, F = c->d.ffn;
-    GemvArgs g = c->row.pend ? gemv_norm(c, w->g_attn, first_x_out) : gemv_plain(c->xn, c->xn_lo);
+    GemvArgs g = (c->row.pend || c->row.embed) ? gemv_norm(c, w->g_attn, first_x_out) : gemv_plain(c->xn, c->xn_lo);
     GemmPlan plan = enqueue_gemv(c, g, w->wq, w->wk, w->wv, 3, H, H, st);
-    enqueue_row_attention(c, g.part, plan, kv, ctx_len, st);
-    g = gemv_plain(c->attn, c->attn_lo);
+    g = gemv_attn(c, enqueue_row_attention(c, g.part, plan, kv, ctx_len, st));
     c->row.pend_plan = enqueue_gemv(c, g, w->wo, nullptr, nullptr, 1, H, H, st);
     c->row.pend = g.part;
     if (!has_ffn(w)) return;   // attention-only block
@@ -737,6 +755,7 @@ int cats_lm_head_argmax(cats_ctx* ctx, const float* hidden, int32_t n_rows, cons
     ctx->n0 = 0;
     ctx->rows = n_rows;
     ctx->row.pend = nullptr;
+    ctx->row.embed = nullptr;
     hipStream_t st = as_stream(stream);
     ResidualNormArgs rn;
     rn.x = const_cast<float*>(hidden);  // read only: no source/partials given, so nothing is written back
@@ -923,22 +942,11 @@ int cats_draft_chain(cats_ctx* ctx, const cats_layer_weights* layers, int32_t la
         if (k == gamma && !hidden_out) break;   // the last draft only needs its hidden state
         ctx->n0 = k;
         ctx->rows = 1;
-        ResidualNormArgs rn;
-        rn.x = ctx->x;
-        rn.x_in = nullptr;
-        rn.embed = static_cast<const bf16_t*>(embed);
-        rn.token = ctx->token + k;
-        rn.part = nullptr;
-        rn.plan = GemmPlan{1, GEMM_KC, 1, 1, 1};
-        rn.gain = static_cast<const bf16_t*>(layers[layer_begin].g_attn);
-        rn.xn = ctx->xn;
-        rn.xn_lo = ctx->xn_lo;
-        rn.ss = ctx->ss;
-        rn.T = 1;
-        rn.H = ctx->d.hidden;
-        rn.eps = ctx->d.rms_eps;
-        launch_residual_norm(rn, st);
+        // the row starts as the embedding of token k (written by the step before); the first
+        // product reads it from the table
         ctx->row.x = ctx->x;
+        ctx->row.embed = static_cast<const bf16_t*>(embed);
+        ctx->row.token = ctx->token + k;
         ctx->row.pend = nullptr;
         for (int l = layer_begin; l < layer_end; ++l) enqueue_layer_row(ctx, &layers[l], &kv[l], ctx_len, nullptr, st);
         // the row after the draft layers is written straight into hidden_out: by the adapter's first

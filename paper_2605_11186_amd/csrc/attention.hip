@@ -451,8 +451,8 @@ __global__ __launch_bounds__(64 * W) void cats_tree_attention_kernel(AttnArgs a)
 // heads), 256 threads; a workgroup takes its chunk in passes of DEC_TILE keys (normally one).
 // Nothing here is a matrix product worth a matrix core: a pass is 64 KB of keys and values, and
 // the launch is one memory round trip (partial sums, keys and values are all requested before the
-// first of them is used), a few hundred fused multiply-adds per thread, and the hand-over of the
-// chunk results to the last workgroup of the head.
+// first of them is used), a few hundred fused multiply-adds per thread, and the store of the
+// chunk's result (see DecodeAttnArgs: the following product merges the chunks).
 //   scores: a key row is D/8 16-byte pieces, one per lane, summed over those lanes;
 //   values: the cache is transposed, a dim's 128 keys are 16 16-byte pieces, one per lane.
 // Rows that must stay invisible (later siblings, rows past the tree, the node's own row, which is
@@ -474,7 +474,6 @@ __global__ __launch_bounds__(256) void cats_decode_attention(DecodeAttnArgs a) {
     __shared__ float s_sc[DEC_TILE];
     __shared__ __align__(16) float s_o[D];
     __shared__ float s_new;
-    __shared__ int s_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = blockIdx.x, h = blockIdx.y;
@@ -636,65 +635,16 @@ __global__ __launch_bounds__(256) void cats_decode_attention(DecodeAttnArgs a) {
     }
     __syncthreads();
 
-    // out[h * D + dims] = num / den as high and low bf16 parts, four dims per thread
-    auto write_out = [&](f32x4 num, float den) {
-        const float inv = 1.0f / den;
-        uint2 hi, lo;
-        split_bf2(num[0] * inv, num[1] * inv, hi.x, lo.x);
-        split_bf2(num[2] * inv, num[3] * inv, hi.y, lo.y);
-        *reinterpret_cast<uint2*>(a.out + h * D + 4 * tid) = hi;
-        *reinterpret_cast<uint2*>(a.out_lo + h * D + 4 * tid) = lo;
-    };
-    if (a.n_chunks == 1) {
-        if (tid < D / 4) write_out(*reinterpret_cast<const f32x4*>(&s_o[4 * tid]), l_run);
-        return;
-    }
-    // publish the chunk (device-coherent 16-byte stores, acknowledged before the arrival count is
-    // raised); the head's last workgroup adds the chunks in index order
+    // The chunk's result: unnormalised sums, running maximum and row sum.  The output projection
+    // merges a head's chunks while it builds its input columns, so nothing is handed over between
+    // workgroups here and the launch ends with these stores.
     const size_t slot = static_cast<size_t>(h) * a.n_chunks + chunk;
-    if (tid < D / 4) store_coherent16(a.po + slot * D + 4 * tid, *reinterpret_cast<const f32x4*>(&s_o[4 * tid]));
+    if (tid < D / 4)
+        *reinterpret_cast<f32x4*>(a.po + slot * D + 4 * tid) = *reinterpret_cast<const f32x4*>(&s_o[4 * tid]);
     if (tid == 0) {
-        __hip_atomic_store(a.pml + slot * 2, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(a.pml + slot * 2 + 1, l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.pml[slot * 2] = m_run;
+        a.pml[slot * 2 + 1] = l_run;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (tid == 0)
-        s_last = __hip_atomic_fetch_add(a.arrivals + h, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.n_chunks - 1;
-    __syncthreads();
-    if (!s_last || tid >= D / 4) return;
-    constexpr int MG = 8;
-    float Mg = -1e30f, den = 0.f;
-    f32x4 num = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < a.n_chunks; c0 += MG) {
-        f32x4 v[MG];
-        float mc[MG], lc[MG];
-#pragma unroll
-        for (int j = 0; j < MG; ++j) {
-            const size_t sl = static_cast<size_t>(h) * a.n_chunks + min(c0 + j, a.n_chunks - 1);
-            mc[j] = __hip_atomic_load(a.pml + sl * 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            lc[j] = __hip_atomic_load(a.pml + sl * 2 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            v[j] = load_coherent16(a.po + sl * D + 4 * tid);
-        }
-#pragma unroll
-        for (int j = 0; j < MG; ++j) wait_coherent(v[j]);
-        float Mn = Mg;
-#pragma unroll
-        for (int j = 0; j < MG; ++j) Mn = fmaxf(Mn, mc[j]);
-        const float resc = __builtin_amdgcn_exp2f(Mg - Mn);
-        den *= resc;
-        num *= resc;
-        Mg = Mn;
-#pragma unroll
-        for (int j = 0; j < MG; ++j)
-            if (c0 + j < a.n_chunks) {
-                const float wc = __builtin_amdgcn_exp2f(mc[j] - Mg);
-                den += wc * lc[j];
-                num += wc * v[j];
-            }
-    }
-    write_out(num, den);
-    if (tid == 0) __hip_atomic_store(a.arrivals + h, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
 // Ancestor-or-self set of every node as a 128-bit mask (bit a of anc[i] set when a is on the

@@ -330,12 +330,16 @@ void launch_argmax(const ArgmaxArgs& a, hipStream_t st);
 // columns of its own work items.  Same plan (128-row tiles, 256-wide items), weight layouts and
 // partial-tile layout ([piece][N]) as the GEMM above, so the consumers are the same kernels.
 //   GEMV_PLAIN   X = x_hi + x_lo (a row that a row kernel or the attention kernel has written)
-//   GEMV_NORM    x_out = x_in + sum of the pieces of the product before (residual update);
-//                X = x_out * gain (as high + low bf16 parts, like the row kernel); the workgroup that
-//                owns item (tile 0, chunk c) also writes x_out and ss_out[c] for chunk c's columns
+//   GEMV_NORM    x_out = x_in (or the embedding row of *token) + sum of the pieces of the product
+//                before, if any (residual update); X = x_out * gain (as high + low bf16 parts, like
+//                the row kernel); the workgroup that owns item (tile 0, chunk c) also writes x_out
+//                and ss_out[c] for chunk c's columns
 //   GEMV_SWIGLU  X = silu(g) * u, g | u = norm factor * sums of the pieces of the gate|up product
+//   GEMV_ATTN    X = the attention output of the single query: the key chunks' partial results that
+//                cats_decode_attention left (unnormalised sums, running maximum and row sum per
+//                chunk), merged in chunk order with the usual log-sum-exp rescaling
 // x_in and x_out must not overlap; pend must not be the buffer `part` points into.
-enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_SWIGLU = 2 };
+enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_SWIGLU = 2, GEMV_ATTN = 3 };
 struct GemvArgs {
     const bf16_t* w[3];
     int n_seg, seg_rows, seg_pad;
@@ -345,7 +349,9 @@ struct GemvArgs {
     float* part;         // [pieces][N]
     int mode;
     const bf16_t *x_hi, *x_lo;   // PLAIN: [K]
-    const float* x_in;           // NORM: [K]
+    const float* x_in;           // NORM: [K] (unused when embed is given)
+    const bf16_t* embed;         // NORM, optional: [V][K] table; the row starts as embed[*token]
+    const int32_t* token;        // device, one entry
     float* x_out;                // NORM: [K] or null
     const bf16_t* gain;          // NORM: [K]
     float* ss_out;               // NORM: [SS_STRIDE]
@@ -354,6 +360,9 @@ struct GemvArgs {
     int pend_ld;
     NormScale ns;                // SWIGLU: the norm factor of the row (row 0 of ns.ss)
     int f_pad;                   // SWIGLU: column offset of the up half
+    const float* po;             // ATTN: [K / head_dim][n_chunks][head_dim] unnormalised chunk sums
+    const float* pml;            // ATTN: [K / head_dim][n_chunks][2] running maximum (base 2), row sum
+    int n_chunks, head_dim;      // ATTN
 };
 void launch_gemv(const GemvArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
@@ -396,7 +405,9 @@ constexpr int ATTN_MAX_QGROUPS = CATS_MAX_TREE / ATTN_QN;   // query groups per 
 // decoding) with the q|k|v step folded in: every workgroup adds up the query columns of its head
 // from the q|k|v product's partial sums, scales and rotates them; the workgroup whose key chunk
 // holds the node's own cache row does the same for the key and value columns, appends them to the
-// cache (bf16) and uses them (high + low part) without reading them back.
+// cache (bf16) and uses them (high + low part) without reading them back.  The kernel ends with
+// one partial result per (head, key chunk); the output projection that follows merges them while
+// it builds its input columns (GEMV_ATTN), so no workgroup waits for another.
 constexpr int DEC_TILE = 128;       // keys per pass of a workgroup
 constexpr int DEC_MAX_CHUNKS = 32;  // key chunks per head at most (the context's scratch holds that many)
 struct DecodeAttnArgs {
@@ -410,11 +421,8 @@ struct DecodeAttnArgs {
     int node;            // the query node; keys: rows [0, ctx_len) and ctx_len + j for j <= node on its path
     int H, nh, d, max_ctx, ctx_len;
     int n_chunks, span;  // chunk c owns keys [c * span, (c + 1) * span); span is a multiple of 32
-    float* po;           // [nh][n_chunks][d]
-    float* pml;          // [nh][n_chunks][2]
-    int* arrivals;       // [nh], zero between launches
-    bf16_t* out;         // [H] high parts of the attention output
-    bf16_t* out_lo;      // [H] low parts
+    float* po;           // [nh][n_chunks][d]  unnormalised weighted value sums of the chunk
+    float* pml;          // [nh][n_chunks][2]  running maximum (base 2) and row sum of the chunk
 };
 void launch_decode_attention(const DecodeAttnArgs& a, hipStream_t st);
 void launch_tree_masks(const int32_t* parent, int T, u32x4* anc, hipStream_t st);

@@ -68,11 +68,20 @@ __device__ __forceinline__ void stage_x(const GemvArgs& a, float (*xrow)[GEMV_KC
     } else if (MODE == GEMV_NORM) {
         f32x4 xin[NE], sum[NE];
         uint2 gb[NE];
+        if (a.embed) {   // the row is still its embedding: bf16 -> float32 is exact
+            const bf16_t* row = a.embed + static_cast<size_t>(a.token[0]) * a.K;
 #pragma unroll
-        for (int e = 0; e < NE; ++e) {
-            xin[e] = *reinterpret_cast<const f32x4*>(a.x_in + kk[e]);
-            gb[e] = *reinterpret_cast<const uint2*>(a.gain + kk[e]);
+            for (int e = 0; e < NE; ++e) {
+                const uint2 eb = *reinterpret_cast<const uint2*>(row + kk[e]);
+                xin[e] = f32x4{__uint_as_float(eb.x << 16), __uint_as_float(eb.x & 0xFFFF0000u),
+                               __uint_as_float(eb.y << 16), __uint_as_float(eb.y & 0xFFFF0000u)};
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) xin[e] = *reinterpret_cast<const f32x4*>(a.x_in + kk[e]);
         }
+#pragma unroll
+        for (int e = 0; e < NE; ++e) gb[e] = *reinterpret_cast<const uint2*>(a.gain + kk[e]);
         if (a.pend) {
             const float* pp[NE];
             int np[NE];
@@ -100,6 +109,59 @@ __device__ __forceinline__ void stage_x(const GemvArgs& a, float (*xrow)[GEMV_KC
             gain_split4(val, gb[e], hi, lo);
             xv[e] = join_bf4(hi, lo);
         }
+    } else if (MODE == GEMV_ATTN) {
+        // columns k .. k+3 belong to head k / head_dim; its chunks are merged in index order, MG
+        // chunks' loads in flight at a time, rescaled to the running maximum between groups
+        constexpr int MG = 8;
+        const float* po[NE];
+        const float* ml[NE];
+        f32x4 num[NE];
+        float den[NE], Mg[NE];
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
+            const int h = kk[e] / a.head_dim;
+            po[e] = a.po + static_cast<size_t>(h) * a.n_chunks * a.head_dim + (kk[e] - h * a.head_dim);
+            ml[e] = a.pml + static_cast<size_t>(h) * a.n_chunks * 2;
+            num[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+            den[e] = 0.f;
+            Mg[e] = -1e30f;
+        }
+        for (int c0 = 0; c0 < a.n_chunks; c0 += MG) {
+            f32x4 v[NE][MG];
+            float mc[NE][MG], lc[NE][MG];
+#pragma unroll
+            for (int e = 0; e < NE; ++e)
+#pragma unroll
+                for (int j = 0; j < MG; ++j) {
+                    const int c = min(c0 + j, a.n_chunks - 1);
+                    mc[e][j] = ml[e][2 * c];
+                    lc[e][j] = ml[e][2 * c + 1];
+                    v[e][j] = *reinterpret_cast<const f32x4*>(po[e] + static_cast<size_t>(c) * a.head_dim);
+                }
+            if (c0 == 0) {
+                __builtin_amdgcn_sched_barrier(0);
+                hook();
+            }
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                float Mn = Mg[e];
+#pragma unroll
+                for (int j = 0; j < MG; ++j) Mn = fmaxf(Mn, mc[e][j]);   // clamped repeats do not change the maximum
+                const float resc = __builtin_amdgcn_exp2f(Mg[e] - Mn);
+                den[e] *= resc;
+                num[e] *= resc;
+                Mg[e] = Mn;
+#pragma unroll
+                for (int j = 0; j < MG; ++j)
+                    if (c0 + j < a.n_chunks) {
+                        const float wc = __builtin_amdgcn_exp2f(mc[e][j] - Mn);
+                        den[e] += wc * lc[e][j];
+                        num[e] += wc * v[e][j];
+                    }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < NE; ++e) xv[e] = num[e] * (1.0f / den[e]);
     } else {
         const RowSquares sq = row_squares_load(a.ns, 0);
         const float* pp[2 * NE];
@@ -293,6 +355,8 @@ void launch_gemv(const GemvArgs& a, hipStream_t st, hipEvent_t ev_start, hipEven
         CATS_LAUNCH_M(GEMV_NORM);
     } else if (a.mode == GEMV_SWIGLU) {
         CATS_LAUNCH_M(GEMV_SWIGLU);
+    } else if (a.mode == GEMV_ATTN) {
+        CATS_LAUNCH_M(GEMV_ATTN);
     } else {
         CATS_LAUNCH_M(GEMV_PLAIN);
     }
