@@ -61,6 +61,8 @@ struct cats_ctx {
     int32_t* amax;   // [max_tree]
     float *am_best, *am_second;   // [max_tree][ARGMAX_SLICES] slice results of the argmax
     int *am_idx, *am_arrivals;    // [max_tree][ARGMAX_SLICES] indices, [max_tree] arrival counters (zero between launches)
+    float* am_wg_best;            // [compute units] per-workgroup results of the greedy token inside the
+    int* am_wg_idx;               // single-row LM head product (see GemvArgs::amax)
     // typical acceptance: per node log-sum-exp, entropy, per-slice triples behind them; per node
     // probability of its token at its parent, the threshold there, and the decision
     float *typ_lse = nullptr, *typ_entropy = nullptr, *typ_slice = nullptr, *typ_prob = nullptr, *typ_thr = nullptr;
@@ -440,8 +442,20 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
                      float* margin_out, hipStream_t st, bool typical = false) {
     GemmPlan plan;
     const float* part = c->part;
-    if (c->rows == 1 && c->row.pend) {   // the final norm's residual update rides in the product
-        GemvArgs g = gemv_norm(c, c->row.next_gain, nullptr);
+    if (c->rows == 1) {
+        // with a residual update pending, it and the final norm ride in the product
+        GemvArgs g = c->row.pend ? gemv_norm(c, c->row.next_gain, nullptr) : gemv_plain(c->xn, c->xn_lo);
+        // Only the greedy token wanted, and every workgroup of the product ends up with complete
+        // sums (true of the 7B and 13B shapes on 256 compute units): the product picks it itself.
+        if (!logits_out && !margin_out && !typical &&
+            plan_whole_tiles(make_gemm_plan(seg_pad_of(c, c->d.vocab), c->d.hidden, target_wgs(c), gemm_bn(1), gemm_kc(1)))) {
+            g.amax = argmax_out;
+            g.am_best = c->am_wg_best;
+            g.am_idx = c->am_wg_idx;
+            g.am_arrivals = c->am_arrivals;
+            enqueue_gemv(c, g, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
+            return;
+        }
         plan = enqueue_gemv(c, g, w_lm, nullptr, nullptr, 1, c->d.vocab, c->d.hidden, st);
         part = g.part;
     } else {
@@ -593,6 +607,7 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const size_t o_amax = take(Tm * 4);
     const size_t o_sb = take(Tm * ARGMAX_SLICES * 4), o_s2 = take(Tm * ARGMAX_SLICES * 4);
     const size_t o_si = take(Tm * ARGMAX_SLICES * 4), o_arr = take(Tm * 4);   // zero from the memset below
+    const size_t o_wb = take(static_cast<size_t>(c->n_cus) * 4), o_wi = take(static_cast<size_t>(c->n_cus) * 4);
     const size_t o_tl = take(Tm * 4), o_te = take(Tm * 4), o_ts = take(Tm * ARGMAX_SLICES * 3 * 4);
     const size_t o_tp = take(Tm * 4), o_tt = take(Tm * 4), o_tg = take(Tm);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->flat), off);
@@ -638,6 +653,8 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     c->am_second = reinterpret_cast<float*>(b + o_s2);
     c->am_idx = reinterpret_cast<int*>(b + o_si);
     c->am_arrivals = reinterpret_cast<int*>(b + o_arr);
+    c->am_wg_best = reinterpret_cast<float*>(b + o_wb);
+    c->am_wg_idx = reinterpret_cast<int*>(b + o_wi);
     c->typ_lse = reinterpret_cast<float*>(b + o_tl);
     c->typ_entropy = reinterpret_cast<float*>(b + o_te);
     c->typ_slice = reinterpret_cast<float*>(b + o_ts);

@@ -363,7 +363,20 @@ struct GemvArgs {
     const float* po;             // ATTN: [K / head_dim][n_chunks][head_dim] unnormalised chunk sums
     const float* pml;            // ATTN: [K / head_dim][n_chunks][2] running maximum (base 2), row sum
     int n_chunks, head_dim;      // ATTN
+    // Optional, any mode: the product is the LM head and only the greedy token is wanted.  Every
+    // range of the plan must consist of whole tiles (plan_whole_tiles), so that each workgroup holds
+    // complete sums; it then keeps the best of its columns (lowest index among equals; the row's
+    // positive norm factor does not change the order), no partial tile is written, and the last
+    // workgroup to arrive picks the best of all and writes it to amax[0].
+    int32_t* amax;               // null: off
+    float* am_best;              // [n_wgs] scratch
+    int* am_idx;                 // [n_wgs] scratch
+    int* am_arrivals;            // one counter, zero between launches
 };
+// every workgroup's range is a whole number of tiles
+inline bool plan_whole_tiles(const GemmPlan& p) {
+    return p.items % p.n_wgs == 0 && (p.items / p.n_wgs) % p.chunks == 0;
+}
 void launch_gemv(const GemvArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---------------------------------------------------------------- attention

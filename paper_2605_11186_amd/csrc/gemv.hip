@@ -194,6 +194,9 @@ template <bool PACKED, int MODE>
 __global__ __launch_bounds__(512) void cats_gemv_row(GemvArgs a) {
     __shared__ float xrow[GEMV_XI][GEMV_KC];
     __shared__ float red[4][32];
+    __shared__ float s_am_best[4];
+    __shared__ int s_am_idx[4];
+    __shared__ int s_am_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = (tid >> 6) & 3, kg = tid >> 8;
@@ -212,6 +215,8 @@ __global__ __launch_bounds__(512) void cats_gemv_row(GemvArgs a) {
 
     u32x4 wst[2][8];
     float acc0 = 0.f, acc1 = 0.f;
+    float am_best = -INFINITY;   // greedy token among this lane's columns (a.amax given)
+    int am_idx = 0x7fffffff;
 
     for (int base = 0; base < n_items; base += GEMV_XI) {   // one round unless the range is longer than GEMV_XI items
         const int n_round = min(GEMV_XI, n_items - base);
@@ -277,10 +282,17 @@ __global__ __launch_bounds__(512) void cats_gemv_row(GemvArgs a) {
                 v += red[wave][col];                                                                    \
                 const int n = tile * 128 + wave * 32 + col;                                             \
                 if (n < a.N && n % a.seg_pad < a.seg_rows) {                                            \
-                    const int piece = wg - plan_first_wg(a.plan, tile);                                 \
-                    /* write-through, like the GEMM's partial tiles */                                  \
-                    __hip_atomic_store(a.part + static_cast<size_t>(piece) * a.N + n, v, __ATOMIC_RELAXED, \
-                                       __HIP_MEMORY_SCOPE_AGENT);                                       \
+                    if (a.amax) {   /* columns ascend within a lane: strict > keeps the lowest */      \
+                        if (v > am_best) {                                                              \
+                            am_best = v;                                                                \
+                            am_idx = n;                                                                 \
+                        }                                                                               \
+                    } else {                                                                            \
+                        const int piece = wg - plan_first_wg(a.plan, tile);                             \
+                        /* write-through, like the GEMM's partial tiles */                              \
+                        __hip_atomic_store(a.part + static_cast<size_t>(piece) * a.N + n, v, __ATOMIC_RELAXED, \
+                                           __HIP_MEMORY_SCOPE_AGENT);                                   \
+                    }                                                                                   \
                 }                                                                                       \
             }                                                                                           \
             lds_barrier();   /* red is free again before any wave reaches the next tile end */         \
@@ -339,6 +351,62 @@ __global__ __launch_bounds__(512) void cats_gemv_row(GemvArgs a) {
 #undef CATS_STEP
 #undef CATS_LOAD_W
 #undef CATS_ITEM
+    }
+    if (!a.amax) return;
+
+    // Greedy token: best of this workgroup's columns, then the best of all workgroups by the last
+    // one to arrive (results move with device-scope atomics, acknowledged before the count is raised).
+    auto better = [](float ob, int oi, float b, int bi) { return ob > b || (ob == b && oi < bi); };
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(am_best, o);
+        const int oi = __shfl_xor(am_idx, o);
+        if (better(ob, oi, am_best, am_idx)) {
+            am_best = ob;
+            am_idx = oi;
+        }
+    }
+    if (kg == 0 && lane == 0) {
+        s_am_best[wave] = am_best;
+        s_am_idx[wave] = am_idx;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (better(s_am_best[w], s_am_idx[w], am_best, am_idx)) {
+                am_best = s_am_best[w];
+                am_idx = s_am_idx[w];
+            }
+        __hip_atomic_store(a.am_best + wg, am_best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.am_idx + wg, am_idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        s_am_last = __hip_atomic_fetch_add(a.am_arrivals, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    static_cast<int>(gridDim.x) - 1;
+    }
+    __syncthreads();
+    if (!s_am_last || tid >= 64) return;
+    am_best = -INFINITY;
+    am_idx = 0x7fffffff;
+    for (int w = lane; w < static_cast<int>(gridDim.x); w += 64) {
+        const float ob = __hip_atomic_load(a.am_best + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int oi = __hip_atomic_load(a.am_idx + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (better(ob, oi, am_best, am_idx)) {
+            am_best = ob;
+            am_idx = oi;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(am_best, o);
+        const int oi = __shfl_xor(am_idx, o);
+        if (better(ob, oi, am_best, am_idx)) {
+            am_best = ob;
+            am_idx = oi;
+        }
+    }
+    if (lane == 0) {
+        a.amax[0] = am_idx;
+        __hip_atomic_store(a.am_arrivals, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
     }
 }
 

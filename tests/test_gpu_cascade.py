@@ -324,3 +324,54 @@ def test_draft_chain_argument_rules(tiny4):
     assert status(ctx_len=p.max_ctx - 3) == cats.CATS_ECAPACITY
     assert status() == cats.CATS_OK
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("packed", [False, True])
+def test_greedy_token_inside_the_single_row_lm_head(packed):
+    """A single-row LM head call that asks for the token alone takes it inside the product (every
+    workgroup holds complete sums for whole tiles; the last one to arrive picks the best).  It must
+    name the token that the separate argmax kernel names on the logits of the same call, on a
+    vocabulary with a ragged last tile and more tiles than workgroups, and the lowest index among
+    equal logits (two identical weight rows)."""
+    dims = synth.ModelDims(1, 256, 4, 64, 688, 128 * 300 + 11)
+    seed = 991
+    final = synth.final_weights(dims, seed)
+    w = final["w_lm"].copy()
+    rng = np.random.default_rng(seed)
+    desc = cats.ModelDesc(dims.n_layers, dims.hidden, dims.n_heads, dims.head_dim, dims.ffn, dims.vocab, 64, 4,
+                          dims.rms_eps, dims.rope_base, int(packed))
+    ctx = cats.cats_create(desc)
+    try:
+        g = to_dev_bf16_local(final["g_final"])
+        for case in range(6):
+            hidden = torch.from_numpy(synth.random_hidden(dims, seed + case, 1).astype(np.float32)).cuda()
+            wc = w.copy()
+            if case >= 3:   # the winning row once more at a higher and at a lower index
+                ref = synth.f32_from_bf16_bits(wc).astype(np.float64) @ (
+                    hidden.cpu().numpy()[0].astype(np.float64) * synth.f32_from_bf16_bits(final["g_final"]))
+                best = int(ref.argmax())
+                others = [i for i in rng.integers(0, dims.vocab, 8) if i != best]
+                wc[others[0]] = wc[best]
+                wc[others[1]] = wc[best]
+            w_dev = to_dev_bf16_local(wc)
+            if packed:
+                w_dev = cats.cats_pack_matrix(w_dev)
+            tok_alone = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+            tok_full = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+            logits = torch.empty(1, dims.vocab, dtype=torch.float32, device="cuda")
+            cats.cats_lm_head_argmax(ctx, hidden, g, w_dev, tok_alone)
+            cats.cats_lm_head_argmax(ctx, hidden, g, w_dev, tok_full, logits_out=logits)
+            torch.cuda.synchronize()
+            lg = logits.cpu().numpy()[0]
+            assert int(tok_full[0]) == int(np.flatnonzero(lg == lg.max())[0])
+            assert int(tok_alone[0]) == int(tok_full[0]), (case, int(tok_alone[0]), int(tok_full[0]))
+            if case >= 3:
+                assert int(tok_alone[0]) == min(best, others[0], others[1])
+    finally:
+        torch.cuda.synchronize()
+        cats.cats_destroy(ctx)
+
+
+def to_dev_bf16_local(bits):
+    from gpu_common import to_dev_bf16
+    return to_dev_bf16(bits)
