@@ -97,19 +97,6 @@ inline size_t align256(size_t n) { return (n + 255) & ~static_cast<size_t>(255);
 // register footprint lets one 512-thread workgroup live on a CU); cats_create reads the count.
 int target_wgs(const cats_ctx* c) { return c->n_cus; }
 
-// k values per work item and weight rows per tile.  Up to 32 rows, two groups of four waves share
-// a 128-row tile, each multiplying one 128-wide half of a 256-wide item, and add their sums
-// through LDS when the tile ends: the same bytes in flight as with eight waves on 256 rows, but
-// half the bytes of partial sums to write here and to read back in the consumer, paid for with
-// twice the X bytes staged per weight byte.  Measured on one device (7B shapes, per step):
-// T = 1 -2.7 %, T = 8 -3.7 %, T = 16 / 24 -4.3 %, T = 32 -5.2 %; with two accumulator blocks per
-// wave (T = 48, 63) the staging costs more than the partial sums save (+0.7 %).  Larger trees
-// run on 256-row tiles, one 32-row accumulator block per wave for every 32 rows of T (256-row
-// tiles halve the re-reads of X, 128-row tiles halve the number of partial tiles; at T = 63,
-// 128 rows for every product 5.10 ms per step against 5.09 ms).
-int gemm_kc(int rows) { return rows <= 32 ? 2 * GEMM_KC : GEMM_KC; }
-int gemm_bn(int rows) { return rows <= 32 ? 128 : 256; }
-
 // Key chunks per (head, query group): the launch has heads * query groups * chunks workgroups,
 // about one per compute unit (the kernel's register footprint allows one four-wave workgroup
 // per unit); more chunks than that only add hand-over traffic between workgroups.
@@ -166,7 +153,7 @@ GemmPlan enqueue_gemv(cats_ctx* c, GemvArgs& g, const void* w0, const void* w1, 
     g.packed = c->d.packed_weights;
     g.N = n_seg * g.seg_pad;
     g.K = K;
-    g.plan = make_gemm_plan(g.N, K, target_wgs(c), gemm_bn(1), gemm_kc(1));
+    g.plan = make_gemm_plan(g.N, K, target_wgs(c), 1);
     g.part = (g.mode != GEMV_PLAIN && g.pend == c->part) ? c->part_row : c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
@@ -234,7 +221,7 @@ GemmPlan enqueue_gemm(cats_ctx* c, const bf16_t* x, const bf16_t* x_lo, const vo
     g.N = n_seg * g.seg_pad;
     g.K = K;
     g.T = c->rows;
-    g.plan = make_gemm_plan(g.N, K, target_wgs(c), gemm_bn(g.T), gemm_kc(g.T));
+    g.plan = make_gemm_plan(g.N, K, target_wgs(c), g.T);
     g.part = c->part;
     const bool timed = c->prof_on && c->prof_n < CATS_PROF_MAX;
     if (timed) {
@@ -448,7 +435,7 @@ void enqueue_lm_head(cats_ctx* c, const void* w_lm, float* logits_out, int32_t* 
         // Only the greedy token wanted, and every workgroup of the product ends up with complete
         // sums (true of the 7B and 13B shapes on 256 compute units): the product picks it itself.
         if (!logits_out && !margin_out && !typical &&
-            plan_whole_tiles(make_gemm_plan(seg_pad_of(c, c->d.vocab), c->d.hidden, target_wgs(c), gemm_bn(1), gemm_kc(1)))) {
+            plan_whole_tiles(make_gemm_plan(seg_pad_of(c, c->d.vocab), c->d.hidden, target_wgs(c), 1))) {
             g.amax = argmax_out;
             g.am_best = c->am_wg_best;
             g.am_idx = c->am_wg_idx;
@@ -574,12 +561,9 @@ int cats_create(const cats_model_desc* desc, cats_ctx** out) {
     const int shapes[5][2] = {{3 * d.hidden, d.hidden}, {d.hidden, d.hidden}, {2 * pad32(d.ffn), d.hidden},
                               {d.hidden, d.ffn}, {pad32(d.vocab), d.hidden}};
     for (auto& s : shapes)
-        for (int bn : {128, 256})
-            for (int kc : {GEMM_KC, 2 * GEMM_KC}) {
-                if (kc != GEMM_KC && bn != 128) continue;
-                part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
-                                                    make_gemm_plan(s[0], s[1], target_wgs(c), bn, kc))) * s[0]);
-            }
+        for (int rows : {1, 33, 97})   // one row count per tile shape / pairing of the plan
+            part_cols = std::max(part_cols, static_cast<size_t>(gemm_plan_max_pieces(
+                                                make_gemm_plan(s[0], s[1], target_wgs(c), rows))) * s[0]);
     c->part_elems = part_cols * Tm;
     c->attn_max_chunks = 32;
     const size_t t_pad = (Tm + 31) / 32 * 32;

@@ -42,8 +42,9 @@ struct GemmPlan {
     int bn;      // weight rows per tile
     int kc;      // k values per work item (128 or 256)
     int chunks;  // work items (K chunks of kc values) per tile
-    int n_wgs;   // workgroups
+    int n_wgs;   // ranges of work items (one partial tile per range and tile it touches)
     int items;   // tiles * chunks
+    int ts = 1;  // workgroups per range: each takes its own block of X rows (see the GEMM kernel)
 };
 // 32-bit unsigned arithmetic (a 64-bit division costs a few hundred scalar instructions on the
 // device, at the head of every launch): make_gemm_plan guarantees items * n_wgs < 2^31.
@@ -82,7 +83,7 @@ void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipS
 size_t packed_matrix_elems(int rows, int cols);
 constexpr int GEMM_KC = 128;             // k elements per pipeline stage
 constexpr int GEMM_ST = 2;               // register ring depth
-GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc = GEMM_KC);   // bn: 256 or 128 weight rows per tile; kc: 128, or 256 with bn 128
+GemmPlan make_gemm_plan(int N, int K, int target_wgs, int rows);   // rows of X decide the tile shape (see gemm.hip)
 int gemm_plan_max_pieces(const GemmPlan& p);
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 

@@ -15,6 +15,8 @@
 // epilogue kernel adds a tile's pieces in a fixed order.
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace {
@@ -38,7 +40,16 @@ __device__ __forceinline__ void lds_barrier() {
 // groups' sums are added through LDS when a tile (or the workgroup's range) ends, so that a
 // partial tile is 32 * NWR rows high whatever the number of waves.  ST: ring depth.  PACKED:
 // weights come in the packed fragment order (contiguous 1 KB per wave load).
-template <int TB, int NWR, int KG, int ST, bool PACKED>
+// TS: workgroups per range of work items.  With TS = 2 the launch has two workgroups per range,
+// on the same XCD (workgroup b of a launch runs on XCD b % 8, so the pair is b and b + 8): both
+// stream the range's weights, one for the first 32 * TB rows of X and one for the rows behind them.
+// The pair's loads of a weight line meet in the XCD's L2 (the line leaves memory once), and a
+// range is twice as long as with one workgroup each, i.e. half as many partial tiles.  Used for
+// more than 96 rows, where one workgroup per range would need four accumulator blocks per wave
+// (248 registers, 139 KB of staged X): measured at 128 rows 35.7 against 38.7 us per launch
+// (6.24 against 6.84 ms per 7B step); at 80 and 96 rows the pairs are 3 % slower than three
+// accumulator blocks, at 63 rows 7 % slower than two.
+template <int TB, int NWR, int KG, int ST, bool PACKED, int TS = 1>
 __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs a) {
     constexpr int THREADS = 64 * NWR * KG;
     constexpr int BN = 32 * NWR;
@@ -54,7 +65,14 @@ __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = (tid >> 6) % NWR, kg = (tid >> 6) / NWR;
     const int col = lane & 31, g = lane >> 5;
-    const int wg = blockIdx.x;
+    // pairs: with a multiple of eight ranges, blocks b and b + 8 of every group of 16 share a range
+    // (same XCD); otherwise (small products) neighbouring blocks do
+    const int pg = (TS > 1 && (a.plan.n_wgs & 7) == 0) ? 8 : 1;
+    const int wg = TS == 1 ? static_cast<int>(blockIdx.x)
+                           : static_cast<int>(blockIdx.x / (2 * pg) * pg + blockIdx.x % pg);
+    const int t_base = TS == 1 ? 0 : static_cast<int>(blockIdx.x / pg % 2) * 32 * TB;   // first row of X of this workgroup
+    const int T_loc = min(a.T - t_base, 32 * TB);                                           // its rows
+    if (TS > 1 && T_loc <= 0) return;   // (whole workgroup; does not happen with the plans make_gemm_plan hands out)
     const int C = a.plan.chunks;
     const int C128 = (a.K + GEMM_KC - 1) / GEMM_KC;
     (void)C128;
@@ -78,8 +96,8 @@ __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs 
 #pragma unroll
     for (int p = 0; p < XPT; ++p) {
         const int r = xr + XROWS_PER_PASS * p;
-        x_row_ok[p] = r < a.T;
-        x_off[p] = static_cast<size_t>(min(r, a.T - 1)) * a.K;
+        x_row_ok[p] = r < T_loc;
+        x_off[p] = static_cast<size_t>(t_base + min(r, T_loc - 1)) * a.K;
     }
     const int k_last_x = a.K - 8, k_last_w = a.K - 16;
     const int rb_per_seg = a.seg_pad / PACK_ROWS, n_rb_total = a.n_seg * rb_per_seg;  // packed only
@@ -186,13 +204,13 @@ __global__ __launch_bounds__(64 * NWR * KG) void cats_gemm_skinny_bf16(GemmArgs 
                 /* term through an empty asm ties them to this block.                            */ \
                 int g_here = g;                                                                     \
                 asm volatile("" : "+v"(g_here));                                                    \
-                float* out = a.part + static_cast<size_t>(piece) * a.T * a.N + n;                   \
+                float* out = a.part + (static_cast<size_t>(piece) * a.T + t_base) * a.N + n;        \
                 _Pragma("unroll") for (int tb = 0; tb < TB; ++tb)                                   \
                     _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                \
                     const int t = tb * 32 + 8 * (r >> 2) + 4 * g_here + (r & 3);            \
                     /* write-through store: the partial tile goes on to memory at once instead   */ \
                     /* of waiting, dirty, in the XCD's L2 for the write-back at the kernel's end */ \
-                    if (t < a.T)                                                                    \
+                    if (t < T_loc)                                                                  \
                         __hip_atomic_store(out + static_cast<size_t>(t) * a.N, acc[tb][r], __ATOMIC_RELAXED, \
                                            __HIP_MEMORY_SCOPE_AGENT);                               \
                 }                                                                                   \
@@ -276,34 +294,55 @@ void launch_pack_matrix(const bf16_t* src, bf16_t* dst, int rows, int cols, hipS
                        src, dst, rows, cols, C, n_vec);
 }
 
-// The work items are cut into n equal contiguous ranges, one per workgroup, and the launch lasts
-// as long as the longest range: ceil(items / n) item times.  The product is bound by memory
-// bandwidth, so what counts is how much of n * ceil(items / n) is real work, not how many
+// Tile shape and workgroups per range by the number of rows of X.
+// Up to 32 rows, two groups of four waves share a 128-row tile, each multiplying one 128-wide half
+// of a 256-wide item, and add their sums through LDS when the tile ends: the same bytes in flight
+// as with eight waves on 256 rows, but half the bytes of partial sums to write here and to read
+// back in the consumer, paid for with twice the X bytes staged per weight byte.  Measured on one
+// device (7B shapes, per step): T = 1 -2.7 %, T = 8 -3.7 %, T = 16 / 24 -4.3 %, T = 32 -5.2 %; with
+// two accumulator blocks per wave (T = 48, 63) the staging costs more than the partial sums save
+// (+0.7 %).  Larger trees run on 256-row tiles, one 32-row accumulator block per wave for every 32
+// rows of T up to 96 (256-row tiles halve the re-reads of X, 128-row tiles halve the number of
+// partial tiles; at T = 63, 128 rows for every product 5.10 ms per step against 5.09 ms), and beyond
+// 96 rows as pairs of workgroups with two blocks each (see TS at the kernel).
+static int plan_kc(int rows) { return rows <= 32 ? 2 * GEMM_KC : GEMM_KC; }
+static int plan_bn(int rows) { return rows <= 32 ? 128 : 256; }
+static int plan_ts(int rows) { return rows > 96 ? 2 : 1; }
+
+// The work items are cut into n equal contiguous ranges, one per workgroup (or pair), and the
+// launch lasts as long as the longest range: ceil(items / n) item times.  The product is bound by
+// memory bandwidth, so what counts is how much of n * ceil(items / n) is real work, not how many
 // compute units are busy (measured: 224 instead of 256 busy units cost 2 %).  n is therefore
 // the count in [3/4 target, target] with the fewest item slots, idle units priced in.  7B down
 // projection: 1376 items, 256 workgroups would run 6 items each with 10 % of the slots empty;
-// 230 workgroups run 5.98.
-GemmPlan make_gemm_plan(int N, int K, int target_wgs, int bn, int kc) {
+// 230 workgroups run 5.98.  With pairs, target is half the workgroups and n a multiple of eight
+// (the kernel then finds a pair's range from the block index in groups of 16, one pair per XCD).
+GemmPlan make_gemm_plan(int N, int K, int target_wgs, int rows) {
     GemmPlan p;
-    p.bn = bn;
-    p.kc = kc;
-    p.chunks = (K + kc - 1) / kc;
-    const int tiles = (N + bn - 1) / bn;
+    p.bn = plan_bn(rows);
+    p.kc = plan_kc(rows);
+    p.ts = 1;
+    p.chunks = (K + p.kc - 1) / p.kc;
+    const int tiles = (N + p.bn - 1) / p.bn;
     p.items = tiles * p.chunks;
     // the device-side plan arithmetic is 32-bit: items * workgroups stays far below 2^31 for every
     // supported shape (at most 128 Ki rows x 8 Ki columns per product)
     if (static_cast<long long>(p.items) * target_wgs >= (1ll << 31)) target_wgs = static_cast<int>((1ll << 31) / p.items) - 1;
-    if (target_wgs >= p.items) {
+    const int ts = plan_ts(rows);
+    p.ts = ts;
+    const int step = (ts > 1 && target_wgs / ts >= 8) ? 8 : 1;
+    const int target = std::max(1, target_wgs / ts / step * step);
+    if (target >= p.items) {
         p.n_wgs = p.items;
         return p;
     }
     // cost = item slots, weighted by the measured price of idle compute units (0.07 % each)
     auto cost = [&](int n) {
-        return static_cast<double>((p.items + n - 1) / n) * n * (1.0 + 0.0007 * (target_wgs - n));
+        return static_cast<double>((p.items + n - 1) / n) * n * (1.0 + 0.0007 * ts * (target - n));
     };
-    int best = target_wgs;
-    double best_cost = cost(target_wgs);
-    for (int n = target_wgs - 1; n >= target_wgs - target_wgs / 4 && n >= 1; --n) {
+    int best = target;
+    double best_cost = cost(target);
+    for (int n = target - step; n >= target - target / 4 && n >= step; n -= step) {
         const double c = cost(n);
         if (c < best_cost) {
             best_cost = c;
@@ -329,9 +368,9 @@ int gemm_plan_max_pieces(const GemmPlan& p) {
 void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
     // one 32-row block of X per 32 rows of T; 8 waves: on 256-row tiles, or as two k groups on
     // 128-row tiles (the plan says which); 4 waves on 128-row tiles are kept for experiments
-    const int tb = (a.T + 31) / 32;
+    const int tb = (a.T + 32 * a.plan.ts - 1) / (32 * a.plan.ts);
     const int nwr = a.plan.bn / 32, kgs = a.plan.kc / GEMM_KC;
-    const dim3 grid(a.plan.n_wgs), block(64 * nwr * kgs);
+    const dim3 grid(a.plan.n_wgs * a.plan.ts), block(64 * nwr * kgs);
 #define CATS_LAUNCH_V(TBV, NWRV, KGV)                                                                   \
     if (a.packed)                                                                                       \
         hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, GEMM_ST, true>), grid, block, 0, st,    \
@@ -339,7 +378,16 @@ void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEven
     else                                                                                                \
         hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, NWRV, KGV, GEMM_ST, false>), grid, block, 0, st,   \
                               ev_start, ev_stop, 0, a)
-    if (nwr == 4 && kgs == 2) {
+#define CATS_LAUNCH_TS(TBV)                                                                             \
+    if (a.packed)                                                                                       \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, 8, 1, GEMM_ST, true, 2>), grid, block, 0, st,      \
+                              ev_start, ev_stop, 0, a);                                                 \
+    else                                                                                                \
+        hipExtLaunchKernelGGL((cats_gemm_skinny_bf16<TBV, 8, 1, GEMM_ST, false, 2>), grid, block, 0, st,     \
+                              ev_start, ev_stop, 0, a)
+    if (a.plan.ts == 2) {   // make_gemm_plan grants it beyond 96 rows: two blocks of X per workgroup
+        CATS_LAUNCH_TS(2);
+    } else if (nwr == 4 && kgs == 2) {
         if (tb == 1) {
             CATS_LAUNCH_V(1, 4, 2);
         } else {
@@ -356,11 +404,10 @@ void launch_gemm(const GemmArgs& a, hipStream_t st, hipEvent_t ev_start, hipEven
             CATS_LAUNCH_V(1, 8, 1);
         } else if (tb == 2) {
             CATS_LAUNCH_V(2, 8, 1);
-        } else if (tb == 3) {
+        } else {   // up to 96 rows (beyond that the plan asks for pairs)
             CATS_LAUNCH_V(3, 8, 1);
-        } else {
-            CATS_LAUNCH_V(4, 8, 1);
         }
     }
 #undef CATS_LAUNCH_V
+#undef CATS_LAUNCH_TS
 }
