@@ -206,7 +206,7 @@ def test_13b_layer_shape_three_layers():
         pair.close()
 
 
-@pytest.mark.parametrize("T,S", [(128, 1024), (16, 512), (96, 4096), (1, 1024)])
+@pytest.mark.parametrize("T,S", [(128, 1024), (97, 512), (16, 512), (96, 4096), (1, 1024)])
 def test_7b_layer_shape_tree_and_context_sweep(T, S):
     """Tree sizes on both sides of the GEMM's accumulator variants and long contexts,
     two 7B-shaped layers each."""

@@ -114,10 +114,11 @@ def odd(request):
     p.close()
 
 
-@pytest.mark.parametrize("T", [9, 31, 40, 70, 100, 128])
+@pytest.mark.parametrize("T", [9, 31, 40, 70, 96, 97, 100, 128])
 def test_odd_chunk_counts_every_accumulator_depth(odd, T):
-    """One to four accumulator blocks per wave (and the two-k-group variant up to 32 rows) on
-    shapes whose k range does not divide into whole items."""
+    """One to three accumulator blocks per wave (and the two-k-group variant up to 32 rows), and
+    beyond 96 rows the paired workgroups (two blocks each; the second of a pair has 33 rows at
+    T = 97), on shapes whose k range does not divide into whole items."""
     S = 37
     parent, depth = synth.random_tree(T, 8, T)
     tok = synth.distinct_sibling_tokens(parent, ODD.vocab, T)
