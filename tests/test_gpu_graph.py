@@ -73,3 +73,57 @@ def test_verify_call_replays_from_a_graph(packed):
                 assert snapshot(other)[3] == want[3]
     finally:
         pair.close()
+
+
+def test_draft_chain_replays_from_a_graph():
+    """The stage-1 draft loop (single-row kernels: products that build their own input, the
+    one-launch attention, the LM head that names the token itself through an arrival counter)
+    enqueues kernels and one device-to-device copy only; replays must give the eager call's
+    tokens and hidden states bit for bit, with eager calls in between."""
+    from gpu_common import to_dev_bf16
+    pair = Pair(synth.TINY, SEED + 1, max_ctx=320, max_tree=16, packed=True)
+    try:
+        d = pair.dims
+        S, gamma, root = 70, 5, 123
+        ad = synth.adapter_weights(d, SEED + 2, 0)
+        d_ad = cats.pack_layer({k: to_dev_bf16(v) for k, v in ad.items() if k != "g_out"})
+        g_out = to_dev_bf16(ad["g_out"])
+        ad_arr = cats.layer_array([d_ad])
+        kc, vc = pair.oracle_cache_random(SEED, S)
+        ks, vs = pair.device_cache_from_oracle(kc, vc, S)
+        kv_arr = cats.kv_array(ks, vs)
+        ka, va = pair.device_cache_from_oracle(kc, vc, S)   # a second set: its first layer is the adapter block's cache
+        kv_ad = cats.kv_array(ka[:1], va[:1])
+
+        def enqueue_chain(tokens, hidden, stream):
+            cats.cats_draft_chain(pair.ctx, pair.layers_arr, 0, pair.L, ad_arr, g_out, pair.d_final["w_lm"],
+                                  pair.d_embed, kv_arr, kv_ad, S, root, gamma, tokens, hidden_out=hidden,
+                                  stream=stream)
+
+        def fresh():
+            return (torch.full((gamma + 1,), -1, dtype=torch.int32, device="cuda"),
+                    torch.zeros(gamma + 1, d.hidden, dtype=torch.float32, device="cuda"))
+
+        stream = torch.cuda.Stream()
+        (t_eager, h_eager), (t_other, h_other), (t_rep, h_rep) = fresh(), fresh(), fresh()
+        with torch.cuda.stream(stream):
+            enqueue_chain(t_eager, h_eager, stream)
+            torch.cuda.synchronize()
+            want_t, want_h = t_eager.cpu().numpy().copy(), h_eager.cpu().numpy().copy()
+            assert want_t[0] == root and (want_t[1:] >= 0).all()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                enqueue_chain(t_rep, h_rep, stream)
+            torch.cuda.synchronize()
+            for _ in range(4):
+                t_rep.fill_(-1)
+                h_rep.zero_()
+                enqueue_chain(t_other, h_other, stream)     # eager work between the replays
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert np.array_equal(t_rep.cpu().numpy(), want_t)
+                assert np.array_equal(h_rep.cpu().numpy(), want_h)
+                assert np.array_equal(t_other.cpu().numpy(), want_t)
+    finally:
+        pair.close()
